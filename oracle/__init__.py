@@ -1,0 +1,212 @@
+"""ctypes front end of the CPU oracle (oracle/spin_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by __graft_entry__.smoke() and by
+the cpu_baseline leg of bench.py; never by the GPU package.  All arrays are
+numpy uint64 on the host, party-major ([n][...]).  The wrappers only allocate
+outputs and marshal pointers; every protocol step is in the C file.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "spin_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+# stream ids of the synthetic generator (which tensor a random word belongs to)
+STREAM_X, STREAM_Y, STREAM_A, STREAM_B, STREAM_C = 1, 2, 3, 4, 5
+STREAM_R, STREAM_RTOP, STREAM_RMSB = 6, 7, 8
+
+
+def build(force=True):
+    """Compile the oracle with gcc (-O2, OpenMP for the row loops)."""
+    stale = not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+             "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = ctypes.CDLL(_LIB)
+        u64, sz, i32, p = ctypes.c_uint64, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p
+        L.oracle_rand64.restype = u64
+        L.oracle_rand64.argtypes = [u64, u64, u64, u64]
+        L.oracle_absorb.restype = u64
+        L.oracle_absorb.argtypes = [u64, u64]
+        L.oracle_encode.argtypes = [p, sz, i32, i32, p]
+        L.oracle_decode.argtypes = [p, sz, i32, i32, p]
+        L.oracle_share.argtypes = [p, sz, i32, i32, u64, u64, p]
+        L.oracle_open.argtypes = [p, p, sz, i32, i32, p]
+        L.oracle_ring_matmul.argtypes = [p, p, i32, i32, i32, i32, p]
+        L.oracle_dealer_matmul.argtypes = [i32, i32, i32, i32, i32, i32, u64, u64, u64, u64] + [p] * 6
+        L.oracle_dealer_mul.argtypes = [i32, sz, i32, u64, u64, u64, u64, p, p, p, p]
+        L.oracle_beaver_matmul.argtypes = [i32] * 6 + [p] * 8 + [p, i32]
+        L.oracle_beaver_mul.argtypes = [i32, sz, i32] + [p] * 6
+        L.oracle_trunc_dealer.argtypes = [i32, sz, i32, i32, u64, u64, u64, u64, p, p, p, p]
+        L.oracle_trunc.argtypes = [i32, sz, i32, i32] + [p] * 5
+        L.oracle_local_shift_trunc.argtypes = [i32, sz, i32, p, p]
+        L.oracle_threads.restype = i32
+        for name in ("oracle_encode", "oracle_decode", "oracle_share", "oracle_open",
+                     "oracle_ring_matmul", "oracle_dealer_matmul", "oracle_dealer_mul",
+                     "oracle_beaver_matmul", "oracle_beaver_mul", "oracle_trunc_dealer",
+                     "oracle_trunc", "oracle_local_shift_trunc"):
+            getattr(L, name).restype = None
+        _lib = L
+    return _lib
+
+
+def _u64(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.uint64:
+        a = a.view(np.uint64) if a.dtype == np.int64 else a.astype(np.uint64)
+    return a
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p) if a is not None else None
+
+
+def threads():
+    return int(lib().oracle_threads())
+
+
+def rand64(seed, stream, party, idx):
+    return int(lib().oracle_rand64(seed, stream, party, idx))
+
+
+def encode(x, p, l=64):
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    out = np.empty(x.shape, dtype=np.uint64)
+    lib().oracle_encode(_ptr(x), x.size, p, l, _ptr(out))
+    return out
+
+
+def decode(u, p, l=64):
+    u = _u64(u)
+    out = np.empty(u.shape, dtype=np.float64)
+    lib().oracle_decode(_ptr(u), u.size, p, l, _ptr(out))
+    return out
+
+
+def share(x, n, seed, stream, l=64):
+    x = _u64(x)
+    out = np.empty((n,) + x.shape, dtype=np.uint64)
+    lib().oracle_share(_ptr(x), x.size, n, l, seed, stream, _ptr(out))
+    return out
+
+
+def open_(shares, mask=None, l=64):
+    shares = _u64(shares)
+    n = shares.shape[0]
+    out = np.empty(shares.shape[1:], dtype=np.uint64)
+    if mask is not None:
+        mask = _u64(mask)
+        assert mask.shape == shares.shape
+    lib().oracle_open(_ptr(shares), _ptr(mask), out.size, n, l, _ptr(out))
+    return out
+
+
+def ring_matmul(P, Q, l=64):
+    P, Q = _u64(P), _u64(Q)
+    M, K = P.shape
+    K2, N = Q.shape
+    assert K == K2
+    out = np.empty((M, N), dtype=np.uint64)
+    lib().oracle_ring_matmul(_ptr(P), _ptr(Q), M, N, K, l, _ptr(out))
+    return out
+
+
+def dealer_matmul(n, batch, M, N, K, seed, l=64):
+    A = np.empty((n, batch, M, K), dtype=np.uint64)
+    B = np.empty((n, batch, K, N), dtype=np.uint64)
+    C = np.empty((n, batch, M, N), dtype=np.uint64)
+    sa = np.empty((batch, M, K), dtype=np.uint64)
+    sb = np.empty((batch, K, N), dtype=np.uint64)
+    sc = np.empty((batch, M, N), dtype=np.uint64)
+    lib().oracle_dealer_matmul(n, batch, M, N, K, l, seed, STREAM_A, STREAM_B, STREAM_C,
+                               _ptr(A), _ptr(B), _ptr(C), _ptr(sa), _ptr(sb), _ptr(sc))
+    return A, B, C
+
+
+def dealer_mul(n, count, seed, l=64):
+    a = np.empty((n, count), dtype=np.uint64)
+    b = np.empty((n, count), dtype=np.uint64)
+    c = np.empty((n, count), dtype=np.uint64)
+    s = np.empty((count,), dtype=np.uint64)
+    lib().oracle_dealer_mul(n, count, l, seed, STREAM_A, STREAM_B, STREAM_C,
+                            _ptr(a), _ptr(b), _ptr(c), _ptr(s))
+    return a, b, c
+
+
+def beaver_matmul(X, Y, A, B, C, l=64, rows=None, return_opened=False):
+    """X,A [n][batch][M][K]; Y,B [n][batch][K][N]; C [n][batch][M][N] -> Z.
+
+    rows: optional int array of output rows to compute (Z then has n_rows rows)."""
+    X, Y, A, B, C = map(_u64, (X, Y, A, B, C))
+    n, batch, M, K = X.shape
+    N = Y.shape[3]
+    assert Y.shape == (n, batch, K, N) and A.shape == X.shape and B.shape == Y.shape
+    assert C.shape == (n, batch, M, N)
+    E = np.empty((batch, M, K), dtype=np.uint64)
+    F = np.empty((batch, K, N), dtype=np.uint64)
+    if rows is None:
+        Z = np.empty((n, batch, M, N), dtype=np.uint64)
+        rp, nr = None, 0
+    else:
+        rows = np.ascontiguousarray(rows, dtype=np.int32)
+        assert rows.min() >= 0 and rows.max() < M
+        Z = np.empty((n, batch, rows.size, N), dtype=np.uint64)
+        rp, nr = _ptr(rows), rows.size
+    lib().oracle_beaver_matmul(n, batch, M, N, K, l, _ptr(X), _ptr(Y), _ptr(A), _ptr(B), _ptr(C),
+                               _ptr(Z), _ptr(E), _ptr(F), rp, nr)
+    return (Z, E, F) if return_opened else Z
+
+
+def beaver_mul(x, y, a, b, c, l=64):
+    x, y, a, b, c = map(_u64, (x, y, a, b, c))
+    n = x.shape[0]
+    count = x[0].size
+    z = np.empty(x.shape, dtype=np.uint64)
+    lib().oracle_beaver_mul(n, count, l, _ptr(x), _ptr(y), _ptr(a), _ptr(b), _ptr(c), _ptr(z))
+    return z
+
+
+def trunc_dealer(n, count, f, seed, l=64):
+    r = np.empty((n, count), dtype=np.uint64)
+    rt = np.empty((n, count), dtype=np.uint64)
+    rm = np.empty((n, count), dtype=np.uint64)
+    s = np.empty((count,), dtype=np.uint64)
+    lib().oracle_trunc_dealer(n, count, l, f, seed, STREAM_R, STREAM_RTOP, STREAM_RMSB,
+                              _ptr(r), _ptr(rt), _ptr(rm), _ptr(s))
+    return r, rt, rm
+
+
+def trunc(x, r, r_top, r_msb, f, l=64):
+    x, r, r_top, r_msb = map(_u64, (x, r, r_top, r_msb))
+    n = x.shape[0]
+    count = x[0].size
+    out = np.empty(x.shape, dtype=np.uint64)
+    lib().oracle_trunc(n, count, l, f, _ptr(x), _ptr(r), _ptr(r_top), _ptr(r_msb), _ptr(out))
+    return out
+
+
+def local_shift_trunc(x, f):
+    x = _u64(x)
+    n = x.shape[0]
+    out = np.empty(x.shape, dtype=np.uint64)
+    lib().oracle_local_shift_trunc(n, x[0].size, f, _ptr(x), _ptr(out))
+    return out
+
+
+def absorb(h, v):
+    return int(lib().oracle_absorb(h, v))
