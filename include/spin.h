@@ -1,0 +1,129 @@
+/*
+ * spin.h -- C ABI of the MI355X (gfx950) library for the per-party local work
+ * of additive-secret-sharing multiplication over the ring Z_2^64:
+ * sharing, opening, the Beaver-triple share update for matrix and elementwise
+ * products, and fixed-point truncation.
+ *
+ * Conventions that hold for every entry point
+ * -------------------------------------------
+ *  - Ring elements are uint64_t; all arithmetic wraps mod 2^64.  Read as signed
+ *    they are the range [-2^63, 2^63-1] of Section 4.1 (Notations).
+ *  - All n parties live on the one GPU.  Share tensors are party-major:
+ *    T[i] is party i's share, contiguous, so a tensor of `count` elements is
+ *    laid out [n][count].  Party 0 is the paper's party 1: it holds residual
+ *    shares and adds every public term.
+ *  - Every data pointer is a DEVICE pointer, 16-byte aligned, owned by the
+ *    caller; the library never allocates, frees or keeps a pointer.  Buffers
+ *    must not overlap unless a function says an output may alias an input.
+ *  - Calls are asynchronous: work is enqueued on `stream` (a hipStream_t; NULL
+ *    is the default stream) and the function returns without synchronising.
+ *  - Errors are return codes.  Arguments are validated before anything is
+ *    launched, so SPIN_EINVAL / SPIN_ERANGE / SPIN_EWORKSPACE never leave
+ *    partial work behind.  Nothing throws across the boundary.
+ *  - 1 <= n <= SPIN_MAX_PARTIES.
+ */
+#ifndef SPIN_H
+#define SPIN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPIN_MAX_PARTIES 8
+
+typedef enum {
+    SPIN_OK = 0,
+    SPIN_EINVAL = 1,     /* null pointer, n out of range, non-positive size, f out of range, misaligned */
+    SPIN_ERANGE = 2,     /* a size whose element count or padded extent does not fit the index types  */
+    SPIN_EWORKSPACE = 3, /* workspace missing or smaller than spin_beaver_matmul_workspace_bytes()    */
+    SPIN_EHIP = 4        /* a launch failed; spin_last_hip_error() holds the runtime's message        */
+} spin_status;
+
+typedef enum {
+    SPIN_GEMM_LIMB_MFMA = 0, /* exact 8-bit-limb decomposition on int8 MFMA, int32 accumulation */
+    SPIN_GEMM_VALU = 1       /* 64-bit multiply-add on the vector ALU (baseline)                */
+} spin_gemm_path;
+
+typedef void *spin_stream; /* hipStream_t */
+
+/* Synthetic randomness.  The paper's parties draw masks and triples in an
+ * OT-based offline phase (Section 4.2); here a stateless counter generator
+ * stands in:  mix(z) is the SplitMix64 finaliser, absorb(h,v) =
+ * mix(h + (v+1)*0x9E3779B97F4A7C15), and
+ *   rand64(seed, stream_id, party, idx) =
+ *       absorb(absorb(absorb(absorb(0, seed), stream_id), party), idx).
+ * out[k] = rand64(seed, stream_id, party, first_idx + k), k < count.          */
+spin_status spin_random(uint64_t *out, size_t count, uint64_t seed, uint64_t stream_id,
+                        uint64_t party, uint64_t first_idx, spin_stream stream);
+
+/* n-out-of-n arithmetic sharing (Section 4.1): x = sum_i x_i.
+ * shares[i][k] = rand64(seed, stream_id, i, k) for i >= 1 and
+ * shares[0][k] = x[k] - sum_{i>=1} shares[i][k].
+ * x: [count] in; shares: [n][count] out.                                      */
+spin_status spin_share(const uint64_t *x, size_t count, int n, uint64_t seed, uint64_t stream_id,
+                       uint64_t *shares, spin_stream stream);
+
+/* Opening (Section 4.1 reconstruction; with a mask, the E = X - A opening of
+ * Section 4.3 Multiplication): out[k] = sum_i (shares[i][k] - mask[i][k]).
+ * The network exchange of the paper is a reduction over the party axis here.
+ * shares, mask: [n][count] in (mask may be NULL = zeros); out: [count].       */
+spin_status spin_open(const uint64_t *shares, const uint64_t *mask, size_t count, int n,
+                      uint64_t *out, spin_stream stream);
+
+/* Online phase of matrix multiplication with a matrix Beaver triple
+ * (Section 4.3 Multiplication; batched as in Section 7.4).  For every batch
+ * entry: E = sum_i (X_i - A_i), F = sum_i (Y_i - B_i), then
+ *     Z_i = C_i + E.B_i + A_i.F   and party 0 adds E.F once.
+ * Row-major operands: X, A [n][batch][M][K]; Y, B [n][batch][K][N];
+ * C, Z [n][batch][M][N].  Z may alias C.  A transposed right operand
+ * (Q.K^T) is passed already transposed.
+ * workspace: device scratch of at least
+ * spin_beaver_matmul_workspace_bytes(n,batch,M,N,K,path) bytes, 256-byte
+ * aligned; its contents are overwritten.  Any K is accepted: the limb path
+ * splits the inner dimension so that no int32 partial sum can overflow.       */
+spin_status spin_beaver_matmul(int n, int batch, int M, int N, int K,
+                               const uint64_t *X, const uint64_t *Y,
+                               const uint64_t *A, const uint64_t *B, const uint64_t *C,
+                               uint64_t *Z, spin_gemm_path path,
+                               void *workspace, size_t workspace_bytes, spin_stream stream);
+
+/* Bytes of workspace spin_beaver_matmul needs; 0 if the arguments are invalid. */
+size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path);
+
+/* Online phase of elementwise multiplication with scalar triples (Section 4.3;
+ * the "batch multiplication" of Section 7.3):
+ *     e = sum_i (x_i - a_i), f = sum_i (y_i - b_i),
+ *     z_i = c_i + e*b_i + a_i*f  (+ e*f for i = 0).
+ * x, y, a, b, c: [n][count] in; z: [n][count] out; z may alias any input.     */
+spin_status spin_beaver_mul(int n, size_t count,
+                            const uint64_t *x, const uint64_t *y,
+                            const uint64_t *a, const uint64_t *b, const uint64_t *c,
+                            uint64_t *z, spin_stream stream);
+
+/* Signed probabilistic truncation by f bits (Section 4.4 Truncation):
+ * Truncate(x,f) = UnsignedTruncate(x + 2^62, 64, f) - 2^(62-f), correct up to
+ * one unit for x in [-2^62, 2^62-1] and undefined (not an error) outside.
+ * The dealer tuple per element is a random ring element r with sharings of r,
+ * of r_top = bits f..62 of r and of r_msb = bit 63 of r.  Steps:
+ *     c = sum_i (x_i + r_i) + 2^62;  c_msb = c >> 63;  c' = bits f..62 of c;
+ *     b_i   = r_msb_i + [i=0] c_msb - 2 c_msb r_msb_i;
+ *     out_i = [i=0] c' - r_top_i + 2^(63-f) b_i - [i=0] 2^(62-f).
+ * x, r, r_top, r_msb: [n][count] in; out: [n][count], may alias x.
+ * 1 <= f <= 61.                                                               */
+spin_status spin_trunc(int n, size_t count, int f, const uint64_t *x,
+                       const uint64_t *r, const uint64_t *r_top, const uint64_t *r_msb,
+                       uint64_t *out, spin_stream stream);
+
+/* Static description of a status code. */
+const char *spin_status_string(spin_status status);
+
+/* Message of the most recent HIP failure seen by this thread ("" if none). */
+const char *spin_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPIN_H */

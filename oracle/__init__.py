@@ -56,6 +56,8 @@ def lib():
         L.oracle_trunc.argtypes = [i32, sz, i32, i32] + [p] * 5
         L.oracle_local_shift_trunc.argtypes = [i32, sz, i32, p, p]
         L.oracle_threads.restype = i32
+        L.oracle_random.argtypes = [p, sz, u64, u64, u64, u64]
+        L.oracle_random.restype = None
         for name in ("oracle_encode", "oracle_decode", "oracle_share", "oracle_open",
                      "oracle_ring_matmul", "oracle_dealer_matmul", "oracle_dealer_mul",
                      "oracle_beaver_matmul", "oracle_beaver_mul", "oracle_trunc_dealer",
@@ -210,3 +212,9 @@ def local_shift_trunc(x, f):
 
 def absorb(h, v):
     return int(lib().oracle_absorb(h, v))
+
+
+def random(count, seed, stream, party, first=0):
+    out = np.empty((count,), dtype=np.uint64)
+    lib().oracle_random(_ptr(out), count, seed, stream, party, first)
+    return out

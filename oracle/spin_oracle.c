@@ -346,3 +346,9 @@ int oracle_threads(void) { return 1; }
  * SplitMix64 sequences: absorb(h, v) is output number v of SplitMix64 started
  * from state h. */
 u64 oracle_absorb(u64 h, u64 v) { return absorb(h, v); }
+
+/* out[k] = rand64(seed, stream, party, first + k): a whole generator stream at once. */
+void oracle_random(u64 *out, size_t count, u64 seed, u64 stream, u64 party, u64 first)
+{
+    for (size_t k = 0; k < count; ++k) out[k] = oracle_rand64(seed, stream, party, first + k);
+}

@@ -1,0 +1,58 @@
+// Shared host/device helpers of the gfx950 library: the counter generator,
+// 16-byte ring vectors, launch bookkeeping.  Internal; the public surface is
+// include/spin.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/spin.h"
+
+namespace spin {
+
+typedef uint64_t u64;
+typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+
+// ---- counter generator (specified in include/spin.h at spin_random) --------
+__host__ __device__ inline u64 mix64(u64 z)
+{
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27; z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+__host__ __device__ inline u64 absorb(u64 h, u64 v) { return mix64(h + (v + 1) * 0x9E3779B97F4A7C15ull); }
+// Everything of rand64 that does not depend on the element index.
+inline u64 stream_key(u64 seed, u64 stream_id, u64 party)
+{
+    return absorb(absorb(absorb(0, seed), stream_id), party);
+}
+
+struct PartyKeys { u64 key[SPIN_MAX_PARTIES]; };
+
+// ---- launch bookkeeping ------------------------------------------------------
+void note_hip_error(hipError_t e, const char *where);
+// Returns SPIN_OK or records the launch error and returns SPIN_EHIP.
+spin_status check_launch(const char *where);
+
+// ---- internal launchers (defined in the .hip files) -------------------------
+spin_status launch_random(u64 *out, size_t count, u64 key, u64 first_idx, hipStream_t s);
+spin_status launch_share(const u64 *x, size_t count, int n, const PartyKeys &keys, u64 *shares, hipStream_t s);
+spin_status launch_open(const u64 *shares, const u64 *mask, size_t count, int n, u64 *out, hipStream_t s);
+spin_status launch_beaver_mul(int n, size_t count, const u64 *x, const u64 *y, const u64 *a, const u64 *b,
+                              const u64 *c, u64 *z, hipStream_t s);
+spin_status launch_trunc(int n, size_t count, int f, const u64 *x, const u64 *r, const u64 *r_top,
+                         const u64 *r_msb, u64 *out, hipStream_t s);
+
+struct MatmulArgs {
+    int n, batch, M, N, K;
+    const u64 *X, *Y, *A, *B, *C;
+    u64 *Z;
+    void *workspace;
+};
+size_t valu_workspace_bytes(int n, int batch, int M, int N, int K);
+spin_status launch_matmul_valu(const MatmulArgs &a, hipStream_t s);
+size_t limb_workspace_bytes(int n, int batch, int M, int N, int K);
+spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s);
+
+}  // namespace spin

@@ -1,0 +1,370 @@
+// Exact ring GEMM over Z_2^64 on the int8 matrix cores.
+//
+// Every uint64 a is rewritten as eight balanced digits s_0..s_7 in [-128,127]
+// with  sum_i s_i 256^i == a  (mod 2^64)   [t = a + 0x80..80; s = t ^ 0x80..80].
+// Then  a*b == sum_{i+j<=7} s_i t_j 256^(i+j)  (mod 2^64): the 28 digit pairs
+// with i+j >= 8 are multiples of 2^64.  The 36 surviving pairs are int8 x int8
+// products; pairs of one diagonal d = i+j share an int32 MFMA accumulator D_d,
+// and the result is  sum_d (int64)D_d << 8d  (mod 2^64).
+//
+// int32 headroom: |s_i t_j| <= 2^14.  D_d needs 64-8d exact bits, so only
+// d <= 3 must not overflow: (d+1) * Ktot * 2^14 < 2^31  <=>  Ktot < 2^15.
+// For d >= 4 only the low 32 bits matter and the accumulators wrap (two's
+// complement), which leaves those bits right.  The host splits the inner
+// dimension into chunks of at most kMaxChunkTiles k-tiles per operand pair.
+//
+// Two kernels:
+//  pack_kernel   opens E (or F), converts E/A_i (or F/B_i') to digits and
+//                stores them as 1 KiB MFMA fragments: [slot][batch][blk][kt]
+//                [digit][lane*16 + j] = digit of element (blk*32 + lane%32,
+//                kt*32 + 16*(lane/32) + j).  Zero padded to whole tiles.
+//  limb_gemm_kernel  per party: Z_i = C_i + [E | A_i] . [B_i' ; F], fragments
+//                streamed global -> LDS with direct-to-LDS loads, 36 MFMAs per
+//                32x32x32 step into 8 diagonal accumulators, recombined once.
+#include "common.hpp"
+
+namespace spin {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned int u32;
+
+constexpr int kFrag = 1024;          // bytes of one 32x32 int8 fragment
+constexpr int kDigits = 8;
+constexpr int kMaxChunkTiles = 511;  // 2*511*32 = 32704 < 2^15 digit products per accumulator
+
+// ------------------------------------------------------------------ pack ---
+__device__ inline u64 to_digits(u64 a)
+{
+    return (a + 0x8080808080808080ull) ^ 0x8080808080808080ull;
+}
+
+// Transposes 16 digit-words (16 elements x 8 digits) into 8 rows of 16 bytes
+// and stores row p at dst + p*kFrag.
+__device__ inline void store_digit_rows(const u64 (&w)[16], char *dst)
+{
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {          // digits 0-3 from the low words, 4-7 from the high words
+        u32 rows[4][4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            u32 w0 = (u32)(w[4 * q + 0] >> (32 * half)), w1 = (u32)(w[4 * q + 1] >> (32 * half));
+            u32 w2 = (u32)(w[4 * q + 2] >> (32 * half)), w3 = (u32)(w[4 * q + 3] >> (32 * half));
+            // 4x4 byte transpose with v_perm_b32 (selector 0-3: second operand, 4-7: first operand)
+            u32 t0 = __builtin_amdgcn_perm(w1, w0, 0x05010400u);   // w0.b0 w1.b0 w0.b1 w1.b1
+            u32 t1 = __builtin_amdgcn_perm(w1, w0, 0x07030602u);   // w0.b2 w1.b2 w0.b3 w1.b3
+            u32 t2 = __builtin_amdgcn_perm(w3, w2, 0x05010400u);
+            u32 t3 = __builtin_amdgcn_perm(w3, w2, 0x07030602u);
+            rows[0][q] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
+            rows[1][q] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+            rows[2][q] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
+            rows[3][q] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            v4i v = {(int)rows[p][0], (int)rows[p][1], (int)rows[p][2], (int)rows[p][3]};
+            *(v4i *)(dst + (size_t)(half * 4 + p) * kFrag) = v;
+        }
+    }
+}
+
+struct PackArgs {
+    const u64 *val;     // X or Y shares   [n][batch][R][Cc]
+    const u64 *tri;     // A or B shares   [n][batch][R][Cc]
+    char *pack;         // [n+1][batch][nblk][KT][8][1024]
+    int n, batch;
+    int rows, cols;     // source matrix is rows x cols, row-major
+    int nblk, KT;       // blocks of 32 along the non-contracted axis; k-tiles of 32
+};
+
+// BSIDE = false: source is M x K (left operands); a fragment row is a matrix row.
+// BSIDE = true : source is K x N (right operands); a fragment row is a matrix column.
+// blockIdx.y = 0 opens sum_i (val_i - tri_i) into slot 0 and, having party 0's
+// triple share in registers anyway, writes it to slot 1 (left side: A_0; right
+// side: B_0 + F, which folds the public E.F into party 0's first product).
+// blockIdx.y = i >= 1 converts party i's triple share into slot i+1.
+template <bool BSIDE, int NP>
+__global__ __launch_bounds__(256) void pack_kernel(PackArgs a)
+{
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const long tile = (long)blockIdx.x * 4 + wave;          // (blk, kt) pair
+    if (tile >= (long)a.nblk * a.KT) return;
+    const int blk = (int)(tile / a.KT), kt = (int)(tile % a.KT);
+    const int b = blockIdx.z;
+    const int rc = blk * 32 + (lane % 32);                  // row (left) / column (right) in the matrix
+    const int k0 = kt * 32 + 16 * (lane / 32);
+    const int K = BSIDE ? a.rows : a.cols;
+    const int RC = BSIDE ? a.cols : a.rows;
+    const size_t mat = (size_t)a.rows * a.cols;
+    const size_t party_stride = (size_t)a.batch * mat;
+
+    auto elem = [&](int j) -> size_t {
+        return BSIDE ? (size_t)(k0 + j) * a.cols + rc : (size_t)rc * a.cols + (k0 + j);
+    };
+    auto frag = [&](int slot) -> char * {
+        return a.pack + ((((size_t)slot * a.batch + b) * a.nblk + blk) * a.KT + kt) * (kDigits * kFrag) + lane * 16;
+    };
+    const bool rc_ok = rc < RC;
+
+    if (blockIdx.y == 0) {
+        u64 opened[16], first[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) { opened[j] = 0; first[j] = 0; }
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const u64 *v = a.val + (size_t)i * party_stride + (size_t)b * mat;
+            const u64 *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                if (rc_ok && k0 + j < K) {
+                    u64 tv = t[elem(j)];
+                    opened[j] += v[elem(j)] - tv;
+                    if (i == 0) first[j] = tv;
+                }
+            }
+        }
+        u64 w[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) w[j] = to_digits(opened[j]);
+        store_digit_rows(w, frag(0));
+#pragma unroll
+        for (int j = 0; j < 16; ++j) w[j] = to_digits(BSIDE ? first[j] + opened[j] : first[j]);
+        store_digit_rows(w, frag(1));
+    } else {
+        const int i = blockIdx.y;                           // party 1..n-1 -> slot i+1
+        const u64 *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
+        u64 w[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) w[j] = to_digits((rc_ok && k0 + j < K) ? t[elem(j)] : 0);
+        store_digit_rows(w, frag(i + 1));
+    }
+}
+
+// ------------------------------------------------------------------ GEMM ---
+struct GemmArgs {
+    const char *packA;   // [n+1][batch][nblkA][KT][8][1024]: slot 0 = E, slot 1+i = A_i
+    const char *packB;   // [n+1][batch][nblkB][KT][8][1024]: slot 0 = F, slot 1+i = B_i'
+    const u64 *C;        // [n][batch][M][N]  (or Z itself for the later k-chunks)
+    u64 *Z;
+    int n, batch, M, N;
+    int nblkA, nblkB, KT;
+    int kt0, ktn;        // this launch covers k-tiles [kt0, kt0+ktn) of both operand pairs
+    int tilesM, tilesN;
+};
+
+template <int WM, int WN, int NSTAGE>
+struct GemmShape {
+    static constexpr int BM = 2 * 32 * WM, BN = 2 * 32 * WN;     // 4 waves as 2 x 2
+    static constexpr int FA = BM / 32 * kDigits, FB = BN / 32 * kDigits;
+    static constexpr int stage_bytes = (FA + FB) * kFrag;
+    static constexpr int lds_bytes = NSTAGE * stage_bytes;
+    static constexpr int loads_per_wave = (FA + FB) / 4;
+};
+
+template <int WM, int WN, int NSTAGE>
+__global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
+{
+    using S = GemmShape<WM, WN, NSTAGE>;
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+    const int lane = threadIdx.x % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+    const int wm = wave / 2, wn = wave % 2;
+
+    // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tiles so
+    // that workgroups sharing an L2 also share operand fragments, and walk that range in 4-tile-tall
+    // column strips.
+    const int per_mat = g.tilesM * g.tilesN;
+    const long total = (long)per_mat * g.n * g.batch;
+    long id = blockIdx.x;
+    {
+        const long chunk = (total + 7) / 8;
+        const long full = total - (chunk - 1) * 8;       // XCDs that own `chunk` tiles (the rest own chunk-1)
+        const int xcd = (int)(id % 8);
+        const long within = id / 8;
+        id = xcd < full ? xcd * chunk + within : full * chunk + (xcd - full) * (chunk - 1) + within;
+    }
+    const int pb = (int)(id / per_mat);                  // party * batch + b
+    int t = (int)(id % per_mat);
+    const int party = pb / g.batch, b = pb % g.batch;
+    constexpr int GROUP = 4;
+    const int strip = t / (GROUP * g.tilesN);
+    const int strip_h = min(GROUP, g.tilesM - strip * GROUP);
+    t -= strip * GROUP * g.tilesN;
+    const int tm = strip * GROUP + t % strip_h, tn = t / strip_h;
+
+    // fragment streams: step < ktn uses (E, B_i'), step >= ktn uses (A_i, F)
+    const size_t slotA = (size_t)g.batch * g.nblkA * g.KT * (kDigits * kFrag);
+    const size_t slotB = (size_t)g.batch * g.nblkB * g.KT * (kDigits * kFrag);
+    const char *a_first = g.packA + (size_t)b * g.nblkA * g.KT * (kDigits * kFrag);   // E
+    const char *a_second = a_first + (size_t)(1 + party) * slotA;                      // A_i
+    const char *b_second = g.packB + (size_t)b * g.nblkB * g.KT * (kDigits * kFrag);  // F
+    const char *b_first = b_second + (size_t)(1 + party) * slotB;                      // B_i'
+
+    const int steps = 2 * g.ktn;
+    auto issue_loads = [&](int step, int stage) {
+        const int second = step >= g.ktn;
+        const int kt = g.kt0 + (second ? step - g.ktn : step);
+        const char *as = second ? a_second : a_first, *bs = second ? b_second : b_first;
+        char *dst = lds + stage * S::stage_bytes;
+#pragma unroll
+        for (int q = 0; q < S::loads_per_wave; ++q) {
+            const int f = q * 4 + wave;                  // fragment index within the stage
+            const char *src;
+            if (f < S::FA) {
+                const int blk = tm * (S::BM / 32) + f / kDigits;
+                src = as + ((size_t)blk * g.KT + kt) * (kDigits * kFrag) + (f % kDigits) * kFrag;
+            } else {
+                const int fb = f - S::FA;
+                const int blk = tn * (S::BN / 32) + fb / kDigits;
+                src = bs + ((size_t)blk * g.KT + kt) * (kDigits * kFrag) + (fb % kDigits) * kFrag;
+            }
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)(src + lane * 16),
+                                             (void __attribute__((address_space(3))) *)(dst + f * kFrag), 16, 0, 0);
+        }
+    };
+
+    v16i acc[WM][WN][kDigits];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int d = 0; d < kDigits; ++d)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][d][r] = 0;
+
+    issue_loads(0, 0);
+    for (int step = 0; step < steps; ++step) {
+        const int stage = step % NSTAGE;
+        __builtin_amdgcn_s_waitcnt(0);                   // this wave's loads of `step` have landed
+        __syncthreads();                                 // ... and everyone's; stage of step-1 is free
+        const char *sa = lds + stage * S::stage_bytes + (wm * WM * kDigits) * kFrag + lane * 16;
+        const char *sb = lds + stage * S::stage_bytes + (S::FA + wn * WN * kDigits) * kFrag + lane * 16;
+        v4i af[WM][kDigits], bf[WN][kDigits];
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int d = 0; d < kDigits; ++d) bf[j][d] = *(const v4i *)(sb + (j * kDigits + d) * kFrag);
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+#pragma unroll
+            for (int d = 0; d < kDigits; ++d) af[i][d] = *(const v4i *)(sa + (i * kDigits + d) * kFrag);
+        if (step + 1 < steps) issue_loads(step + 1, (step + 1) % NSTAGE);
+#pragma unroll
+        for (int da = 0; da < kDigits; ++da)
+#pragma unroll
+            for (int db = 0; db + da < kDigits; ++db)
+#pragma unroll
+                for (int i = 0; i < WM; ++i)
+#pragma unroll
+                    for (int j = 0; j < WN; ++j)
+                        acc[i][j][da + db] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i][da], bf[j][db],
+                                                                                  acc[i][j][da + db], 0, 0, 0);
+    }
+
+    // recombine the diagonals and add C_i
+    const size_t mat = (size_t)g.M * g.N;
+    const u64 *Cm = g.C + (size_t)pb * mat;
+    u64 *Zm = g.Z + (size_t)pb * mat;
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            const int col = tn * S::BN + (wn * WN + j) * 32 + lane % 32;
+            const int row0 = tm * S::BM + (wm * WM + i) * 32 + 4 * (lane / 32);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = row0 + 8 * (r / 4) + r % 4;
+                u64 v = 0;
+#pragma unroll
+                for (int d = 0; d < kDigits; ++d) v += (u64)(int64_t)acc[i][j][d][r] << (8 * d);
+                if (row < g.M && col < g.N) Zm[(size_t)row * g.N + col] = Cm[(size_t)row * g.N + col] + v;
+            }
+        }
+}
+
+// ------------------------------------------------------------------ host ---
+constexpr int kWM = 2, kWN = 1, kStages = 2;
+using Shape = GemmShape<kWM, kWN, kStages>;
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+struct Plan {
+    int KT, nblkA, nblkB, tilesM, tilesN;
+    size_t packA_bytes, packB_bytes;
+};
+inline Plan make_plan(int n, int batch, int M, int N, int K)
+{
+    Plan p;
+    p.KT = ceil_div(K, 32);
+    p.tilesM = ceil_div(M, Shape::BM);
+    p.tilesN = ceil_div(N, Shape::BN);
+    p.nblkA = p.tilesM * (Shape::BM / 32);
+    p.nblkB = p.tilesN * (Shape::BN / 32);
+    p.packA_bytes = (size_t)(n + 1) * batch * p.nblkA * p.KT * (kDigits * kFrag);
+    p.packB_bytes = (size_t)(n + 1) * batch * p.nblkB * p.KT * (kDigits * kFrag);
+    return p;
+}
+
+template <class F> inline void for_party_count(int n, F &&fn)
+{
+    switch (n) {
+    case 1: fn(std::integral_constant<int, 1>()); break;
+    case 2: fn(std::integral_constant<int, 2>()); break;
+    case 3: fn(std::integral_constant<int, 3>()); break;
+    case 4: fn(std::integral_constant<int, 4>()); break;
+    case 5: fn(std::integral_constant<int, 5>()); break;
+    case 6: fn(std::integral_constant<int, 6>()); break;
+    case 7: fn(std::integral_constant<int, 7>()); break;
+    default: fn(std::integral_constant<int, 8>()); break;
+    }
+}
+
+}  // namespace
+
+size_t limb_workspace_bytes(int n, int batch, int M, int N, int K)
+{
+    Plan p = make_plan(n, batch, M, N, K);
+    return p.packA_bytes + p.packB_bytes;
+}
+
+spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s)
+{
+    const Plan p = make_plan(a.n, a.batch, a.M, a.N, a.K);
+    char *packA = (char *)a.workspace;
+    char *packB = packA + p.packA_bytes;
+
+    PackArgs pa{a.X, a.A, packA, a.n, a.batch, a.M, a.K, p.nblkA, p.KT};
+    PackArgs pb{a.Y, a.B, packB, a.n, a.batch, a.K, a.N, p.nblkB, p.KT};
+    for_party_count(a.n, [&](auto np) {
+        constexpr int NP = decltype(np)::value;
+        dim3 ga((unsigned)(((long)p.nblkA * p.KT + 3) / 4), a.n, a.batch);
+        pack_kernel<false, NP><<<ga, 256, 0, s>>>(pa);
+        dim3 gb((unsigned)(((long)p.nblkB * p.KT + 3) / 4), a.n, a.batch);
+        pack_kernel<true, NP><<<gb, 256, 0, s>>>(pb);
+    });
+    spin_status st = check_launch("spin_beaver_matmul(pack)");
+    if (st != SPIN_OK) return st;
+
+    static bool attr_set = false;
+    auto kernel = limb_gemm_kernel<kWM, kWN, kStages>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           Shape::lds_bytes);
+        if (e != hipSuccess) { note_hip_error(e, "hipFuncSetAttribute"); return SPIN_EHIP; }
+        attr_set = true;
+    }
+    GemmArgs g{packA, packB, a.C, a.Z, a.n, a.batch, a.M, a.N, p.nblkA, p.nblkB, p.KT, 0, 0, p.tilesM, p.tilesN};
+    const long total = (long)p.tilesM * p.tilesN * a.n * a.batch;
+    for (int kt0 = 0; kt0 < p.KT; kt0 += kMaxChunkTiles) {
+        g.kt0 = kt0;
+        g.ktn = p.KT - kt0 < kMaxChunkTiles ? p.KT - kt0 : kMaxChunkTiles;
+        g.C = kt0 == 0 ? a.C : a.Z;                      // later chunks accumulate onto Z
+        kernel<<<(unsigned)total, 256, Shape::lds_bytes, s>>>(g);
+    }
+    return check_launch("spin_beaver_matmul(limb gemm)");
+}
+
+}  // namespace spin

@@ -1,0 +1,134 @@
+// The C ABI of include/spin.h: argument validation, then dispatch to the
+// kernel launchers.  Validation touches no HIP call, so it behaves the same on
+// a machine without a GPU.
+#include <string.h>
+
+#include "common.hpp"
+
+namespace spin {
+
+static thread_local char g_hip_error[256] = "";
+
+void note_hip_error(hipError_t e, const char *where)
+{
+    snprintf(g_hip_error, sizeof g_hip_error, "%s: %s", where, hipGetErrorString(e));
+}
+
+spin_status check_launch(const char *where)
+{
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return SPIN_OK;
+    note_hip_error(e, where);
+    return SPIN_EHIP;
+}
+
+namespace {
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+inline bool bad_ptr(const void *p) { return p == nullptr || !aligned16(p); }
+inline bool bad_n(int n) { return n < 1 || n > SPIN_MAX_PARTIES; }
+// element counts are limited so that n * count * 8 and the grid size stay in range
+constexpr size_t kMaxCount = (size_t)1 << 38;
+}  // namespace
+}  // namespace spin
+
+using namespace spin;
+
+extern "C" {
+
+spin_status spin_random(uint64_t *out, size_t count, uint64_t seed, uint64_t stream_id, uint64_t party,
+                        uint64_t first_idx, spin_stream stream)
+{
+    if (bad_ptr(out) || count == 0) return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    return launch_random(out, count, stream_key(seed, stream_id, party), first_idx, (hipStream_t)stream);
+}
+
+spin_status spin_share(const uint64_t *x, size_t count, int n, uint64_t seed, uint64_t stream_id,
+                       uint64_t *shares, spin_stream stream)
+{
+    if (bad_ptr(x) || bad_ptr(shares) || bad_n(n) || count == 0) return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    PartyKeys keys;
+    for (int i = 0; i < SPIN_MAX_PARTIES; ++i) keys.key[i] = stream_key(seed, stream_id, (u64)i);
+    return launch_share(x, count, n, keys, shares, (hipStream_t)stream);
+}
+
+spin_status spin_open(const uint64_t *shares, const uint64_t *mask, size_t count, int n, uint64_t *out,
+                      spin_stream stream)
+{
+    if (bad_ptr(shares) || bad_ptr(out) || (mask && !aligned16(mask)) || bad_n(n) || count == 0)
+        return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    return launch_open(shares, mask, count, n, out, (hipStream_t)stream);
+}
+
+static spin_status check_matmul_dims(int n, int batch, int M, int N, int K)
+{
+    if (bad_n(n) || batch < 1 || M < 1 || N < 1 || K < 1) return SPIN_EINVAL;
+    // every operand must stay below 2^38 elements per party and the launch grids within HIP's limits
+    const size_t lim = kMaxCount;
+    if ((size_t)batch * M * K > lim || (size_t)batch * K * N > lim || (size_t)batch * M * N > lim)
+        return SPIN_ERANGE;
+    if ((long)n * batch > 65535) return SPIN_ERANGE;
+    if (M > (1 << 24) || N > (1 << 24) || K > (1 << 24)) return SPIN_ERANGE;
+    return SPIN_OK;
+}
+
+size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path)
+{
+    if (check_matmul_dims(n, batch, M, N, K) != SPIN_OK) return 0;
+    if (path == SPIN_GEMM_LIMB_MFMA) return limb_workspace_bytes(n, batch, M, N, K);
+    if (path == SPIN_GEMM_VALU) return valu_workspace_bytes(n, batch, M, N, K);
+    return 0;
+}
+
+spin_status spin_beaver_matmul(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Y,
+                               const uint64_t *A, const uint64_t *B, const uint64_t *C, uint64_t *Z,
+                               spin_gemm_path path, void *workspace, size_t workspace_bytes, spin_stream stream)
+{
+    if (bad_ptr(X) || bad_ptr(Y) || bad_ptr(A) || bad_ptr(B) || bad_ptr(C) || bad_ptr(Z)) return SPIN_EINVAL;
+    if (path != SPIN_GEMM_LIMB_MFMA && path != SPIN_GEMM_VALU) return SPIN_EINVAL;
+    spin_status st = check_matmul_dims(n, batch, M, N, K);
+    if (st != SPIN_OK) return st;
+    const size_t need = spin_beaver_matmul_workspace_bytes(n, batch, M, N, K, path);
+    if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need)
+        return SPIN_EWORKSPACE;
+    MatmulArgs a{n, batch, M, N, K, X, Y, A, B, C, Z, workspace};
+    return path == SPIN_GEMM_LIMB_MFMA ? launch_matmul_limb(a, (hipStream_t)stream)
+                                       : launch_matmul_valu(a, (hipStream_t)stream);
+}
+
+spin_status spin_beaver_mul(int n, size_t count, const uint64_t *x, const uint64_t *y, const uint64_t *a,
+                            const uint64_t *b, const uint64_t *c, uint64_t *z, spin_stream stream)
+{
+    if (bad_ptr(x) || bad_ptr(y) || bad_ptr(a) || bad_ptr(b) || bad_ptr(c) || bad_ptr(z) || bad_n(n) || count == 0)
+        return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    return launch_beaver_mul(n, count, x, y, a, b, c, z, (hipStream_t)stream);
+}
+
+spin_status spin_trunc(int n, size_t count, int f, const uint64_t *x, const uint64_t *r, const uint64_t *r_top,
+                       const uint64_t *r_msb, uint64_t *out, spin_stream stream)
+{
+    if (bad_ptr(x) || bad_ptr(r) || bad_ptr(r_top) || bad_ptr(r_msb) || bad_ptr(out) || bad_n(n) || count == 0)
+        return SPIN_EINVAL;
+    if (f < 1 || f > 61) return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    return launch_trunc(n, count, f, x, r, r_top, r_msb, out, (hipStream_t)stream);
+}
+
+const char *spin_status_string(spin_status status)
+{
+    switch (status) {
+    case SPIN_OK: return "ok";
+    case SPIN_EINVAL: return "invalid argument";
+    case SPIN_ERANGE: return "size out of range";
+    case SPIN_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case SPIN_EHIP: return "HIP launch failure";
+    }
+    return "unknown status";
+}
+
+const char *spin_last_hip_error(void) { return g_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,151 @@
+"""ctypes binding of libspin.so (include/spin.h).  Argument marshalling only:
+every step of the protocol runs in the library's kernels.
+
+Ring tensors are torch.int64 CUDA tensors (the bit pattern of a uint64 ring
+element), party-major ([n, ...]).  Calls are enqueued on torch's current
+stream.  The library must have been built (python -m paper_2402_02320_amd.build);
+there is no fallback: a missing library raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspin.so")
+
+LIMB_MFMA, VALU = 0, 1
+MAX_PARTIES = 8
+
+_lib = None
+
+
+class SpinError(RuntimeError):
+    pass
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise SpinError("%s not found: build it with `python -m paper_2402_02320_amd.build`" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        u64, sz, i32, p = ctypes.c_uint64, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p
+        L.spin_random.argtypes = [p, sz, u64, u64, u64, u64, p]
+        L.spin_share.argtypes = [p, sz, i32, u64, u64, p, p]
+        L.spin_open.argtypes = [p, p, sz, i32, p, p]
+        L.spin_beaver_matmul.argtypes = [i32] * 5 + [p] * 6 + [i32, p, sz, p]
+        L.spin_beaver_matmul_workspace_bytes.argtypes = [i32] * 5 + [i32]
+        L.spin_beaver_matmul_workspace_bytes.restype = sz
+        L.spin_beaver_mul.argtypes = [i32, sz] + [p] * 6 + [p]
+        L.spin_trunc.argtypes = [i32, sz, i32] + [p] * 5 + [p]
+        for name in ("spin_random", "spin_share", "spin_open", "spin_beaver_matmul", "spin_beaver_mul", "spin_trunc"):
+            getattr(L, name).restype = i32
+        L.spin_status_string.argtypes = [i32]
+        L.spin_status_string.restype = ctypes.c_char_p
+        L.spin_last_hip_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != 0:
+        L = lib()
+        msg = L.spin_status_string(status).decode()
+        if status == 4:
+            msg += ": " + L.spin_last_hip_error().decode()
+        raise SpinError(msg)
+
+
+def _dev(t, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int64 and t.is_contiguous()):
+        raise SpinError("%s must be a contiguous torch.int64 CUDA tensor" % name)
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def random(count, seed, stream_id, party, first_idx=0, device="cuda"):
+    out = torch.empty(count, dtype=torch.int64, device=device)
+    _check(lib().spin_random(_dev(out, "out"), count, seed, stream_id, party, first_idx, _stream()))
+    return out
+
+
+def share(x, n, seed, stream_id, out=None):
+    if out is None:
+        out = torch.empty((n,) + tuple(x.shape), dtype=torch.int64, device=x.device)
+    _check(lib().spin_share(_dev(x, "x"), x.numel(), n, seed, stream_id, _dev(out, "shares"), _stream()))
+    return out
+
+
+def open(shares, mask=None, out=None):  # noqa: A001 - named after the C entry point
+    n = shares.shape[0]
+    if out is None:
+        out = torch.empty(tuple(shares.shape[1:]), dtype=torch.int64, device=shares.device)
+    if mask is not None and mask.shape != shares.shape:
+        raise SpinError("mask must have the shape of shares")
+    _check(lib().spin_open(_dev(shares, "shares"), None if mask is None else _dev(mask, "mask"),
+                           out.numel(), n, _dev(out, "out"), _stream()))
+    return out
+
+
+def beaver_matmul_workspace_bytes(n, batch, M, N, K, path=LIMB_MFMA):
+    return int(lib().spin_beaver_matmul_workspace_bytes(n, batch, M, N, K, path))
+
+
+def beaver_matmul(X, Y, A, B, C, path=LIMB_MFMA, out=None, workspace=None):
+    """X, A: [n,batch,M,K]; Y, B: [n,batch,K,N]; C: [n,batch,M,N] -> Z [n,batch,M,N]."""
+    n, batch, M, K = X.shape
+    N = Y.shape[3]
+    if tuple(Y.shape) != (n, batch, K, N) or A.shape != X.shape or B.shape != Y.shape \
+            or tuple(C.shape) != (n, batch, M, N):
+        raise SpinError("inconsistent operand shapes")
+    if out is None:
+        out = torch.empty_like(C)
+    need = beaver_matmul_workspace_bytes(n, batch, M, N, K, path)
+    if need == 0:
+        raise SpinError("invalid matmul dimensions")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+    if not (workspace.is_cuda and workspace.is_contiguous()):
+        raise SpinError("workspace must be a contiguous CUDA tensor")
+    _check(lib().spin_beaver_matmul(n, batch, M, N, K, _dev(X, "X"), _dev(Y, "Y"), _dev(A, "A"), _dev(B, "B"),
+                                    _dev(C, "C"), _dev(out, "Z"), path, workspace.data_ptr(),
+                                    workspace.numel() * workspace.element_size(), _stream()))
+    return out
+
+
+def beaver_mul(x, y, a, b, c, out=None):
+    n = x.shape[0]
+    for t in (y, a, b, c):
+        if t.shape != x.shape:
+            raise SpinError("inconsistent operand shapes")
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib().spin_beaver_mul(n, x[0].numel(), _dev(x, "x"), _dev(y, "y"), _dev(a, "a"), _dev(b, "b"),
+                                 _dev(c, "c"), _dev(out, "z"), _stream()))
+    return out
+
+
+def trunc(x, r, r_top, r_msb, f, out=None):
+    n = x.shape[0]
+    for t in (r, r_top, r_msb):
+        if t.shape != x.shape:
+            raise SpinError("inconsistent operand shapes")
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib().spin_trunc(n, x[0].numel(), f, _dev(x, "x"), _dev(r, "r"), _dev(r_top, "r_top"),
+                            _dev(r_msb, "r_msb"), _dev(out, "out"), _stream()))
+    return out
+
+
+# Fixed-point encoding of Section 4.1 (host-side convenience for the harness; not part of the C ABI).
+def encode(x, f):
+    """float64 tensor -> ring tensor holding floor(x * 2^f)."""
+    return torch.floor(torch.ldexp(x.to(torch.float64), torch.tensor(f))).to(torch.int64)
+
+
+def decode(u, f):
+    return torch.ldexp(u.to(torch.float64), torch.tensor(-f))

@@ -1,0 +1,77 @@
+"""The C-ABI library loads without a GPU, exports every symbol include/spin.h
+declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2402_02320_amd import spin
+    if not os.path.exists(spin.LIB_PATH):
+        from paper_2402_02320_amd import build
+        build.build()
+    return spin.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "spin.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spin_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_five_calls():
+    syms = declared_symbols()
+    for name in ("spin_share", "spin_open", "spin_beaver_matmul", "spin_beaver_mul", "spin_trunc"):
+        assert name in syms
+
+
+def test_every_declared_symbol_is_exported(L):
+    for name in declared_symbols():
+        assert getattr(L, name) is not None
+
+
+def test_argument_validation_needs_no_gpu(L):
+    fake = ctypes.c_void_p(0x1000)          # aligned, never dereferenced: validation rejects first
+    odd = ctypes.c_void_p(0x1008)
+    EINVAL, ERANGE, EWORKSPACE = 1, 2, 3
+    assert L.spin_share(None, 8, 2, 1, 1, fake, None) == EINVAL
+    assert L.spin_share(fake, 0, 2, 1, 1, fake, None) == EINVAL
+    assert L.spin_share(fake, 8, 0, 1, 1, fake, None) == EINVAL
+    assert L.spin_share(fake, 8, 9, 1, 1, fake, None) == EINVAL
+    assert L.spin_share(odd, 8, 2, 1, 1, fake, None) == EINVAL
+    assert L.spin_share(fake, 1 << 40, 2, 1, 1, fake, None) == ERANGE
+    assert L.spin_open(fake, None, 8, 9, fake, None) == EINVAL
+    assert L.spin_open(fake, odd, 8, 2, fake, None) == EINVAL
+    assert L.spin_random(None, 8, 1, 1, 1, 0, None) == EINVAL
+    assert L.spin_beaver_mul(2, 8, fake, fake, fake, fake, None, fake, None) == EINVAL
+    assert L.spin_trunc(2, 8, 0, fake, fake, fake, fake, fake, None) == EINVAL
+    assert L.spin_trunc(2, 8, 62, fake, fake, fake, fake, fake, None) == EINVAL
+    assert L.spin_trunc(2, 8, 16, fake, fake, fake, None, fake, None) == EINVAL
+    mm = L.spin_beaver_matmul
+    assert mm(2, 1, 0, 4, 4, fake, fake, fake, fake, fake, fake, 0, fake, 1 << 30, None) == EINVAL
+    assert mm(2, 1, 4, 4, 4, fake, fake, fake, fake, fake, fake, 7, fake, 1 << 30, None) == EINVAL
+    assert mm(2, 1, 4, 4, 4, fake, fake, fake, fake, fake, fake, 0, None, 0, None) == EWORKSPACE
+    assert mm(2, 1, 4, 4, 4, fake, fake, fake, fake, fake, fake, 0, fake, 16, None) == EWORKSPACE
+    assert mm(2, 1, 1 << 25, 4, 4, fake, fake, fake, fake, fake, fake, 0, fake, 1 << 30, None) == ERANGE
+
+
+def test_workspace_query(L):
+    q = L.spin_beaver_matmul_workspace_bytes
+    assert q(0, 1, 4, 4, 4, 0) == 0 and q(2, 1, 4, 4, 4, 5) == 0
+    # VALU path: E and F as plain ring matrices
+    assert q(3, 2, 10, 7, 5, 1) == 8 * 2 * (10 * 5 + 5 * 7)
+    # limb path: n+1 digit-fragment copies of the padded operands, 8 bytes per padded element
+    got = q(5, 1, 4096, 4096, 4096, 0)
+    assert got == 8 * 6 * (4096 * 4096 * 2)
+    assert q(3, 1, 64, 64, 64, 0) >= 8 * 4 * (64 * 64 * 2)
+
+
+def test_status_strings(L):
+    assert L.spin_status_string(0) == b"ok"
+    assert b"workspace" in L.spin_status_string(3)
+    assert L.spin_last_hip_error() == b""

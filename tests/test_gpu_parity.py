@@ -1,0 +1,269 @@
+"""GPU-vs-oracle parity through the C ABI: every share bit-exact on the same
+seeded inputs, at sizes that span several tiles and a ragged tail, on the edge
+cases, and at the benchmark's full sizes (sampled rows where the oracle would
+take too long).  Inputs and expected values come from oracle/ and the workload
+generators only."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2402_02320_amd import spin, workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int64)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy().view(np.uint64)
+
+
+def rand_u64(rng, shape):
+    return rng.integers(0, 1 << 64, size=shape, dtype=np.uint64)
+
+
+# ----------------------------------------------------------------------------- generator / share / open
+@pytest.mark.parametrize("count,first", [(1, 0), (2, 5), (255, 0), (256, 1 << 40), (1000, 3), (65537, 0)])
+def test_random_matches_generator_spec(count, first):
+    got = host(spin.random(count, seed=0xABC, stream_id=4, party=2, first_idx=first))
+    assert (got == oracle.random(count, 0xABC, 4, 2, first)).all()
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 8])
+@pytest.mark.parametrize("count", [1, 2, 513, 4096, 100003])
+def test_share_and_open(n, count):
+    rng = np.random.default_rng(count + n)
+    x = rand_u64(rng, count)
+    want = oracle.share(x, n, 77, oracle.STREAM_X)
+    got = spin.share(dev(x), n, 77, oracle.STREAM_X)
+    assert (host(got) == want).all()
+    assert (host(spin.open(got)) == x).all()
+    mask = rand_u64(rng, (n, count))
+    assert (host(spin.open(got, dev(mask))) == oracle.open_(want, mask)).all()
+
+
+# ----------------------------------------------------------------------------- elementwise Beaver mul / trunc
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("count", [1, 2, 777, 70000])
+def test_beaver_mul(n, count):
+    rng = np.random.default_rng(1000 * n + count)
+    x, y = rand_u64(rng, (n, count)), rand_u64(rng, (n, count))
+    a, b, c = oracle.dealer_mul(n, count, seed=5)
+    want = oracle.beaver_mul(x, y, a, b, c)
+    got = spin.beaver_mul(dev(x), dev(y), dev(a), dev(b), dev(c))
+    assert (host(got) == want).all()
+    # in place on x
+    xd = dev(x)
+    spin.beaver_mul(xd, dev(y), dev(a), dev(b), dev(c), out=xd)
+    assert (host(xd) == want).all()
+
+
+@pytest.mark.parametrize("n,f", [(1, 16), (2, 16), (3, 16), (5, 16), (8, 16), (3, 1), (2, 61), (5, 26)])
+@pytest.mark.parametrize("count", [1, 2, 999, 65536 + 2])
+def test_trunc(n, f, count):
+    rng = np.random.default_rng(n * 100 + f + count)
+    xs = rng.integers(-(1 << 62), 1 << 62, size=count, dtype=np.int64)
+    xs[0] = -(1 << 62)
+    X = oracle.share(xs.view(np.uint64), n, 91, oracle.STREAM_X)
+    r, rt, rm = oracle.trunc_dealer(n, count, f, seed=91)
+    want = oracle.trunc(X, r, rt, rm, f)
+    Xd = dev(X)
+    got = spin.trunc(Xd, dev(r), dev(rt), dev(rm), f)
+    assert (host(got) == want).all()
+    spin.trunc(Xd, dev(r), dev(rt), dev(rm), f, out=Xd)          # in place
+    assert (host(Xd) == want).all()
+
+
+# ----------------------------------------------------------------------------- Beaver matmul
+def matmul_case(n, batch, M, N, K, seed, path, X=None, Y=None, consistent=True):
+    rng = np.random.default_rng(seed)
+    if X is None:
+        X, Y = rand_u64(rng, (n, batch, M, K)), rand_u64(rng, (n, batch, K, N))
+    if consistent:
+        A, B, C = oracle.dealer_matmul(n, batch, M, N, K, seed=seed)
+    else:
+        A, B, C = rand_u64(rng, X.shape), rand_u64(rng, Y.shape), rand_u64(rng, (n, batch, M, N))
+    want = oracle.beaver_matmul(X, Y, A, B, C)
+    got = spin.beaver_matmul(dev(X), dev(Y), dev(A), dev(B), dev(C), path=path)
+    torch.cuda.synchronize()
+    return host(got), want
+
+
+PATHS = [pytest.param(spin.LIMB_MFMA, id="limb"), pytest.param(spin.VALU, id="valu")]
+SHAPES = [(1, 1, 1, 1, 1), (2, 1, 1, 1, 1), (3, 1, 64, 64, 64), (2, 1, 33, 31, 32), (3, 2, 130, 70, 45),
+          (1, 1, 128, 64, 32), (5, 1, 129, 65, 33), (8, 1, 40, 40, 40), (4, 3, 17, 200, 100),
+          (2, 1, 300, 260, 257), (3, 5, 128, 128, 64), (2, 1, 7, 5, 1000)]
+
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("n,batch,M,N,K", SHAPES)
+def test_beaver_matmul_small_shapes(n, batch, M, N, K, path):
+    got, want = matmul_case(n, batch, M, N, K, seed=n * 7 + M, path=path)
+    assert (got == want).all()
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_beaver_matmul_in_place_on_c(path):
+    rng = np.random.default_rng(3)
+    n, batch, M, N, K = 3, 2, 96, 80, 72
+    X, Y = rand_u64(rng, (n, batch, M, K)), rand_u64(rng, (n, batch, K, N))
+    A, B, C = oracle.dealer_matmul(n, batch, M, N, K, seed=3)
+    Cd = dev(C)
+    spin.beaver_matmul(dev(X), dev(Y), dev(A), dev(B), Cd, path=path, out=Cd)
+    assert (host(Cd) == oracle.beaver_matmul(X, Y, A, B, C)).all()
+
+
+def test_limb_path_worst_case_digits_and_inner_dimension_split():
+    # every digit of every operand equal to -128 (value 0x7F7F7F7F7F7F7F80), with K large enough that
+    # the inner dimension is split into more than one accumulation chunk: the int32 partial sums run
+    # at their proven extreme.  E = X - A and F = Y - B are forced to that value with zero triples.
+    n, M, N, K = 2, 32, 32, 16352 + 96
+    worst = np.uint64(0x7F7F7F7F7F7F7F80)
+    X = np.zeros((n, 1, M, K), dtype=np.uint64); X[0] = worst
+    Y = np.zeros((n, 1, K, N), dtype=np.uint64); Y[0] = worst
+    A = np.zeros_like(X); B = np.zeros_like(Y); A[1] = worst; B[1] = worst   # A_1.F and E.B_1 extreme too
+    X[1] = worst; Y[1] = worst                                               # so that E = F = worst
+    C = np.zeros((n, 1, M, N), dtype=np.uint64)
+    want = oracle.beaver_matmul(X, Y, A, B, C)
+    got = spin.beaver_matmul(dev(X), dev(Y), dev(A), dev(B), dev(C), path=spin.LIMB_MFMA)
+    assert (host(got) == want).all()
+    # and random data across the split
+    got, want = matmul_case(2, 1, 40, 36, 16352 + 40, seed=9, path=spin.LIMB_MFMA, consistent=False)
+    assert (got == want).all()
+
+
+def encode_share(x, n, f, seed, stream):
+    return oracle.share(oracle.encode(x, f), n, seed, stream)
+
+
+def fixed_point_pipeline(cfg, gemm_index, X_real, Y_real, path, rows=None):
+    """share -> Beaver matmul -> trunc on the GPU vs the oracle; returns decoded GPU result."""
+    c = workloads.CONFIGS[cfg]
+    n, f = c.n, c.f
+    batch, M, K = X_real.shape
+    N = Y_real.shape[2]
+    xe, ye = oracle.encode(X_real, f), oracle.encode(Y_real, f)
+    # sharing on the GPU must equal the oracle's sharing
+    Xd = spin.share(dev(xe), n, c.seed, oracle.STREAM_X)
+    Yd = spin.share(dev(ye), n, c.seed, oracle.STREAM_Y)
+    X, Y = oracle.share(xe, n, c.seed, oracle.STREAM_X), oracle.share(ye, n, c.seed, oracle.STREAM_Y)
+    assert (host(Xd) == X).all() and (host(Yd) == Y).all()
+    A, B, C = oracle.dealer_matmul(n, batch, M, N, K, seed=c.seed)
+    Zd = spin.beaver_matmul(Xd, Yd, dev(A), dev(B), dev(C), path=path)
+    Zg = host(Zd)
+    if rows is None:
+        Zo = oracle.beaver_matmul(X, Y, A, B, C)
+        assert (Zg == Zo).all()
+        sel = slice(None)
+    else:
+        Zo = oracle.beaver_matmul(X, Y, A, B, C, rows=rows)
+        assert (Zg[:, :, rows] == Zo).all()
+        sel = rows
+    # reconstruction: the shares sum to the plain ring product (plain definition, on the checked rows)
+    zsum = Zg.sum(axis=0, dtype=np.uint64)
+    for b in range(batch):
+        assert (zsum[b][sel] == oracle.ring_matmul(xe[b][sel], ye[b])).all()
+    r, rt, rm = oracle.trunc_dealer(n, batch * M * N, f, seed=c.seed)
+    Td = spin.trunc(Zd.view(n, -1), dev(r), dev(rt), dev(rm), f)
+    Tg = host(Td).reshape(n, batch, M, N)
+    if rows is None:
+        assert (Tg == oracle.trunc(Zo.reshape(n, -1), r, rt, rm, f).reshape(Tg.shape)).all()
+    else:
+        idx = (np.arange(batch)[:, None, None] * M + np.asarray(rows)[None, :, None]) * N + np.arange(N)
+        idx = idx.reshape(-1)
+        want = oracle.trunc(Zo.reshape(n, -1), r[:, idx], rt[:, idx], rm[:, idx], f)
+        assert (Tg[:, :, rows].reshape(n, -1) == want).all()
+    got = oracle.decode(host(spin.open(Td)).reshape(batch, M, N), f)
+    ref = np.matmul(X_real, Y_real)
+    err = np.abs(got - ref)[:, sel].max()
+    assert err <= 2.0 ** -f * (K + 2), err
+    return err
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_config1_full(path):
+    X, Y = workloads.gemm_plaintexts(1)
+    fixed_point_pipeline(1, 0, X, Y, path)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_config2_gemm_full(path):
+    X, Y = workloads.gemm_plaintexts(2)
+    fixed_point_pipeline(2, 0, X, Y, path)
+
+
+def test_config2_vectors_full():
+    c = workloads.CONFIGS[2]
+    n, f, L = c.n, c.f, c.vec
+    xr, yr = workloads.vec_plaintexts(2)
+    X, Y = encode_share(xr, n, f, c.seed, oracle.STREAM_X), encode_share(yr, n, f, c.seed, oracle.STREAM_Y)
+    a, b, cc = oracle.dealer_mul(n, L, seed=c.seed)
+    r, rt, rm = oracle.trunc_dealer(n, L, f, seed=c.seed)
+    zd = spin.beaver_mul(dev(X), dev(Y), dev(a), dev(b), dev(cc))
+    zo = oracle.beaver_mul(X, Y, a, b, cc)
+    assert (host(zd) == zo).all()
+    td = spin.trunc(zd, dev(r), dev(rt), dev(rm), f)
+    assert (host(td) == oracle.trunc(zo, r, rt, rm, f)).all()
+    got = oracle.decode(host(spin.open(td)), f)
+    assert np.abs(got - xr * yr).max() <= 2.0 ** -f * (1 + 2) * max(1.0, np.abs(xr).max(), np.abs(yr).max())
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_config3_conv_shape_eighth_batch(path):
+    # 16 of the 128 images: M = 16384 rows of the same K = 576, N = 64 GEMM, every row checked
+    X, Y = workloads.gemm_plaintexts(3, scale=16 / 128)
+    assert X.shape == (1, 16384, 576)
+    fixed_point_pipeline(3, 0, X, Y, path)
+
+
+def test_config3_conv_shape_full_sampled_rows():
+    X, Y = workloads.gemm_plaintexts(3)
+    assert X.shape == (1, 131072, 576)
+    rows = np.sort(np.random.default_rng(33).choice(131072, 512, replace=False))
+    rows[0], rows[-1] = 0, 131071
+    fixed_point_pipeline(3, 0, X, Y, spin.LIMB_MFMA, rows=rows)
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_config4_attention_full(path):
+    c = workloads.CONFIGS[4]
+    n, f = c.n, c.f
+    Q, KT = workloads.gemm_plaintexts(4, 0)                 # [64,128,64], [64,64,128]  (K already transposed)
+    fixed_point_pipeline(4, 0, Q, KT, path)
+    # P.V with P = decoded truncated scores scaled into a softmax-like range (no softmax: Section 7 is out of scope)
+    P = np.matmul(Q, KT) / 64.0
+    _, V = workloads.gemm_plaintexts(4, 1)
+    fixed_point_pipeline(4, 1, P, V, path)
+
+
+def test_config4_score_tensor_elementwise():
+    c = workloads.CONFIGS[4]
+    n, f, L = c.n, c.f, c.vec
+    xr, yr = workloads.vec_plaintexts(4)
+    X, Y = encode_share(xr, n, f, c.seed, oracle.STREAM_X), encode_share(yr, n, f, c.seed, oracle.STREAM_Y)
+    a, b, cc = oracle.dealer_mul(n, L, seed=c.seed)
+    zo = oracle.beaver_mul(X, Y, a, b, cc)
+    assert (host(spin.beaver_mul(dev(X), dev(Y), dev(a), dev(b), dev(cc))) == zo).all()
+
+
+def test_config5_full_size_sampled_rows():
+    # 5 parties, 4096^3, the launch the benchmark times.  The oracle computes 96 sampled rows of every
+    # party's share; all other steps (sharing, truncation on those rows, reconstruction) are checked too.
+    X, Y = workloads.gemm_plaintexts(5)
+    rows = np.sort(np.random.default_rng(55).choice(4096, 96, replace=False))
+    rows[0], rows[-1] = 0, 4095
+    fixed_point_pipeline(5, 0, X, Y, spin.LIMB_MFMA, rows=rows)
+
+
+def test_paths_agree_on_config5_shape_slice():
+    # both GEMM paths on a 5-party 512 x 4096 x 4096 slice, full comparison against each other
+    rng = np.random.default_rng(56)
+    n, M, N, K = 5, 512, 512, 4096
+    X, Y = dev(rand_u64(rng, (n, 1, M, K))), dev(rand_u64(rng, (n, 1, K, N)))
+    A, B, C = dev(rand_u64(rng, (n, 1, M, K))), dev(rand_u64(rng, (n, 1, K, N))), dev(rand_u64(rng, (n, 1, M, N)))
+    z0 = spin.beaver_matmul(X, Y, A, B, C, path=spin.LIMB_MFMA)
+    z1 = spin.beaver_matmul(X, Y, A, B, C, path=spin.VALU)
+    assert torch.equal(z0, z1)
