@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the Beaver-multiplication hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input:
+share X and Y -> Beaver matmul (open E, F; share update) -> truncate ->
+elementwise Beaver mul of the result with a second shared tensor -> truncate.
+Default workload: configuration 5 (5 parties, 4096^3, f = 16), the headline
+configuration; all inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line (metric: Z_2^64 ring MACs/s of the Beaver matmul, counted
+as n*2*batch*M*N*K per step), with the roofline of the dominant kernel and the
+CPU oracle timed on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0       # MI355X dense int8 MFMA peak, TOP/s (published 5.0 POP/s)
+PEAK_HBM_GBS = 8000.0
+INT8_OPS_PER_RING_MAC = 72    # 36 digit pairs x (multiply + add)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--path", default="limb", choices=["limb", "valu"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, target_s):
+    """The oracle, as it stands, on a bounded row sample of the same workload."""
+    import oracle
+    from paper_2402_02320_amd import workloads
+    c = workloads.CONFIGS[cfg]
+    g = c.gemms[0]
+    Xr, Yr = workloads.gemm_plaintexts(cfg)
+    batch, M, K = Xr.shape
+    N = Yr.shape[2]
+    X = oracle.share(oracle.encode(Xr, c.f), c.n, c.seed, oracle.STREAM_X)
+    Y = oracle.share(oracle.encode(Yr, c.f), c.n, c.seed, oracle.STREAM_Y)
+    A = np.stack([oracle.random(batch * M * K, c.seed, oracle.STREAM_A, i).reshape(batch, M, K) for i in range(c.n)])
+    B = np.stack([oracle.random(batch * K * N, c.seed, oracle.STREAM_B, i).reshape(batch, K, N) for i in range(c.n)])
+    C = np.stack([oracle.random(batch * M * N, c.seed, oracle.STREAM_C, i).reshape(batch, M, N) for i in range(c.n)])
+    threads = oracle.threads()
+
+    def run(nrows):
+        rows = np.linspace(0, M - 1, nrows).astype(np.int32)
+        t0 = time.perf_counter()
+        oracle.beaver_matmul(X, Y, A, B, C, rows=rows)
+        return time.perf_counter() - t0
+    probe_rows = min(M, 2 * threads)
+    t_probe = run(probe_rows)
+    # the opening of E and F is paid once per call whatever the row count; estimate it from a second probe
+    t_probe2 = run(min(M, 4 * threads))
+    per_row = max((t_probe2 - t_probe) / max(1, min(M, 4 * threads) - probe_rows), 1e-9)
+    nrows = int(max(probe_rows, min(M, (target_s - max(t_probe - per_row * probe_rows, 0.0)) / per_row)))
+    nrows = max(threads, nrows // threads * threads)
+    t = run(nrows)
+    macs = (2 * c.n + 1) * batch * nrows * N * K     # the oracle also forms E.F explicitly for party 0
+    credited = 2 * c.n * batch * nrows * N * K
+    return {"value": credited / t, "unit": "ring MAC/s", "cores": threads, "kind": "oracle",
+            "sample": "config %d, %d of %d output rows of every party's share (%.1f s, incl. opening E and F; "
+                      "%.3g ring MACs executed, %.3g credited as n*2*rows*N*K)" % (cfg, nrows, M, t, macs, credited)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (all parties' shares live on one MI355X); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2402_02320_amd import spin, workloads
+    if not os.path.exists(spin.LIB_PATH):
+        from paper_2402_02320_amd import build
+        build.build()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    c = workloads.CONFIGS[args.config]
+    g = c.gemms[0]
+    n, f = c.n, c.f
+    path = spin.LIMB_MFMA if args.path == "limb" else spin.VALU
+    S = {"X": 1, "Y": 2, "A": 3, "B": 4, "C": 5, "R": 6, "RT": 7, "RM": 8, "W": 9}
+
+    # ---- untimed setup: plaintexts, triples and truncation tuples, all resident in HBM -------------
+    Xr, Yr = workloads.gemm_plaintexts(args.config)
+    batch, M, K = Xr.shape
+    N = Yr.shape[2]
+    x = spin.encode(torch.from_numpy(Xr).cuda(), f)
+    y = spin.encode(torch.from_numpy(Yr).cuda(), f)
+    del Xr, Yr
+    szA, szB, szC = batch * M * K, batch * K * N, batch * M * N
+
+    def party_random(count, stream, shape):
+        return torch.stack([spin.random(count, c.seed, stream, i) for i in range(n)]).view((n,) + shape)
+    A = party_random(szA, S["A"], (batch, M, K))
+    B = party_random(szB, S["B"], (batch, K, N))
+    ws_bytes = spin.beaver_matmul_workspace_bytes(n, batch, M, N, K, path)
+    ws1 = torch.empty(spin.beaver_matmul_workspace_bytes(1, batch, M, N, K, path), dtype=torch.uint8, device="cuda")
+    # dealer: C = (sum A_i).(sum B_i) through the library's own ring GEMM (one party, zero triple), then shared
+    a_open, b_open = spin.open(A)[None], spin.open(B)[None]
+    zA, zB, zC = torch.zeros_like(a_open), torch.zeros_like(b_open), torch.zeros((1, batch, M, N), dtype=torch.int64,
+                                                                                device="cuda")
+    c_plain = spin.beaver_matmul(a_open, b_open, zA, zB, zC, path=path, workspace=ws1)
+    C = spin.share(c_plain[0], n, c.seed, S["C"])
+    del a_open, b_open, zA, zB, zC, c_plain, ws1
+
+    def trunc_tuple(count, salt):
+        r_sh = torch.stack([spin.random(count, c.seed + salt, S["R"], i) for i in range(n)])
+        r = spin.open(r_sh)
+        r_top = (r >> f) & ((1 << (63 - f)) - 1)
+        r_msb = (r >> 63) & 1
+        return r_sh, spin.share(r_top, n, c.seed + salt, S["RT"]), spin.share(r_msb, n, c.seed + salt, S["RM"])
+    r1 = trunc_tuple(szC, 0x100)
+    r2 = trunc_tuple(szC, 0x200)
+    # elementwise triple and the second factor of the elementwise product
+    ea = torch.stack([spin.random(szC, c.seed, 11, i) for i in range(n)])
+    eb = torch.stack([spin.random(szC, c.seed, 12, i) for i in range(n)])
+    ec = spin.share(spin.open(ea) * spin.open(eb), n, c.seed, 13)
+    w = spin.share(spin.encode(torch.from_numpy(workloads.vec_plaintexts(args.config, szC)[0]).cuda(), f), n, c.seed,
+                   S["W"])
+
+    Xs = torch.empty((n, batch, M, K), dtype=torch.int64, device="cuda")
+    Ys = torch.empty((n, batch, K, N), dtype=torch.int64, device="cuda")
+    Z = torch.empty((n, batch, M, N), dtype=torch.int64, device="cuda")
+    T = torch.empty((n, szC), dtype=torch.int64, device="cuda")
+    V = torch.empty((n, szC), dtype=torch.int64, device="cuda")
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+
+    def step():
+        spin.share(x, n, c.seed, S["X"], out=Xs)
+        spin.share(y, n, c.seed, S["Y"], out=Ys)
+        spin.beaver_matmul(Xs, Ys, A, B, C, path=path, out=Z, workspace=ws)
+        spin.trunc(Z.view(n, -1), r1[0], r1[1], r1[2], f, out=T)
+        spin.beaver_mul(T, w, ea, eb, ec, out=V)
+        spin.trunc(V, r2[0], r2[1], r2[2], f, out=V)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    spin.profile_reset()
+    spin.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    spin.profile_enable(False)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ring_macs = 2.0 * n * batch * M * N * K
+    kernels = {k: spin.profile_read(k) for k in spin.KERNELS}
+    spin.profile_reset()
+    gemm_key = "gemm_limb" if path == spin.LIMB_MFMA else "gemm_valu"
+    gemm_ms, gemm_launches = kernels[gemm_key]
+    launches_per_step = gemm_launches / args.steps
+    gemm_avg_ms = gemm_ms / gemm_launches
+    if path == spin.LIMB_MFMA:
+        ops_per_launch = ring_macs * INT8_OPS_PER_RING_MAC / launches_per_step
+        achieved = ops_per_launch / (gemm_avg_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "limb_gemm_kernel", "achieved": achieved, "peak": PEAK_INT8_TOPS,
+                    "unit": "TOP/s", "frac": achieved / PEAK_INT8_TOPS, "traffic": None,
+                    "avg_launch_ms": gemm_avg_ms, "launches_per_step": launches_per_step,
+                    "ring_mac_per_s": ring_macs / launches_per_step / (gemm_avg_ms * 1e-3)}
+    else:
+        # 64-bit multiply-add on the vector ALU: 256 CUs x 64 lanes x 4 SIMDs at 2.4 GHz; a ring MAC costs one
+        # v_mad_u64_u32 and two v_mul_lo_u32 (quarter rate each) plus two adds = 14 issue cycles per lane
+        peak = 256 * 4 * 16 * 2.4e9 / 14 / 1e12
+        achieved = ring_macs / launches_per_step / (gemm_avg_ms * 1e-3) / 1e12
+        roofline = {"bound": "alu", "kernel": "valu_gemm_kernel", "achieved": achieved, "peak": peak,
+                    "unit": "T ring MAC/s", "frac": achieved / peak, "traffic": None, "avg_launch_ms": gemm_avg_ms,
+                    "launches_per_step": launches_per_step}
+    # HBM-bound side kernels, for the record: algorithmic bytes / event time
+    el = 8.0 * szC
+    streams = {}
+    per_call_bytes = {"share": (1 + n) * 8.0 * (szA + szB) / 2, "trunc": 5 * n * el, "beaver_mul": 6 * n * el,
+                      "pack": 8.0 * ((2 * n + n + 1) * szA + (2 * n + n + 1) * szB)}
+    for k, b in per_call_bytes.items():
+        ms, cnt = kernels[k]
+        if cnt:
+            streams[k] = {"GB/s": b / (ms / cnt * 1e-3) / 1e9, "frac_hbm": b / (ms / cnt * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                          "avg_ms": ms / cnt}
+    out = {
+        "metric": "Z_2^64 ring MACs/s for Beaver matmul (1 GPU)", "value": ring_macs / (ms_per_step * 1e-3),
+        "unit": "ring MAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64 (int8 digits, int32 accumulate)" if path == spin.LIMB_MFMA else "u64",
+        "data": "synthetic",
+        "config": {"workload": "config %d: %d parties, batch %d, M=%d N=%d K=%d, f=%d, %s; step = share X,Y + Beaver "
+                               "matmul (open+update) + trunc + elementwise Beaver mul + trunc" %
+                               (args.config, n, batch, M, N, K, f, c.dist),
+                   "gemm_path": args.path, "parties": n},
+        "roofline": roofline, "stream_kernels": streams,
+        "limb_roofline_ring_mac_per_s": PEAK_INT8_TOPS * 1e12 / INT8_OPS_PER_RING_MAC,
+    }
+    if not args.no_cpu_baseline:
+        del Xs, Ys, Z, T, V, ws
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

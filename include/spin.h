@@ -117,6 +117,28 @@ spin_status spin_trunc(int n, size_t count, int f, const uint64_t *x,
                        const uint64_t *r, const uint64_t *r_top, const uint64_t *r_msb,
                        uint64_t *out, spin_stream stream);
 
+/* Per-kernel timing for benchmarks (measurement aid, not part of the protocol).
+ * While enabled, every kernel the library launches is bracketed by a pair of
+ * HIP events recorded on the caller's stream; events are created on demand
+ * (this is the one place the library allocates, and only while enabled).
+ * spin_profile_read waits for the recorded events, and returns the summed
+ * duration in milliseconds and the number of launches of one kernel class
+ * since the last spin_profile_reset.  Not thread-safe.                        */
+typedef enum {
+    SPIN_KERNEL_RANDOM = 0,
+    SPIN_KERNEL_SHARE = 1,
+    SPIN_KERNEL_OPEN = 2,
+    SPIN_KERNEL_BEAVER_MUL = 3,
+    SPIN_KERNEL_TRUNC = 4,
+    SPIN_KERNEL_PACK = 5,       /* open + digit split + fragment layout for the limb GEMM */
+    SPIN_KERNEL_GEMM_LIMB = 6,
+    SPIN_KERNEL_GEMM_VALU = 7,
+    SPIN_KERNEL_COUNT = 8
+} spin_kernel;
+void spin_profile_enable(int on);
+spin_status spin_profile_read(spin_kernel kernel, double *total_ms, unsigned *launches);
+void spin_profile_reset(void);
+
 /* Static description of a status code. */
 const char *spin_status_string(spin_status status);
 

@@ -35,6 +35,13 @@ void note_hip_error(hipError_t e, const char *where);
 // Returns SPIN_OK or records the launch error and returns SPIN_EHIP.
 spin_status check_launch(const char *where);
 
+// Brackets the launches made during its lifetime with a HIP event pair when profiling is enabled.
+struct KernelTimer {
+    KernelTimer(spin_kernel id, hipStream_t s);
+    ~KernelTimer();
+    spin_kernel id; hipStream_t stream; hipEvent_t begin; bool active;
+};
+
 // ---- internal launchers (defined in the .hip files) -------------------------
 spin_status launch_random(u64 *out, size_t count, u64 key, u64 first_idx, hipStream_t s);
 spin_status launch_share(const u64 *x, size_t count, int n, const PartyKeys &keys, u64 *shares, hipStream_t s);

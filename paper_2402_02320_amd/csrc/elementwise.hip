@@ -141,6 +141,7 @@ template <class F> inline void for_party_count(int n, F &&fn)
 
 spin_status launch_random(u64 *out, size_t count, u64 key, u64 first_idx, hipStream_t s)
 {
+    KernelTimer timer(SPIN_KERNEL_RANDOM, s);
     if (count % 2 == 0)
         random_kernel<u64x2><<<grid_for(count / 2), kBlock, 0, s>>>((u64x2 *)out, count / 2, key, first_idx);
     else
@@ -150,6 +151,7 @@ spin_status launch_random(u64 *out, size_t count, u64 key, u64 first_idx, hipStr
 
 spin_status launch_share(const u64 *x, size_t count, int n, const PartyKeys &keys, u64 *shares, hipStream_t s)
 {
+    KernelTimer timer(SPIN_KERNEL_SHARE, s);
     for_party_count(n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
         if (count % 2 == 0)
@@ -163,6 +165,7 @@ spin_status launch_share(const u64 *x, size_t count, int n, const PartyKeys &key
 
 spin_status launch_open(const u64 *shares, const u64 *mask, size_t count, int n, u64 *out, hipStream_t s)
 {
+    KernelTimer timer(SPIN_KERNEL_OPEN, s);
     for_party_count(n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
         if (count % 2 == 0) {
@@ -184,6 +187,7 @@ spin_status launch_open(const u64 *shares, const u64 *mask, size_t count, int n,
 spin_status launch_beaver_mul(int n, size_t count, const u64 *x, const u64 *y, const u64 *a, const u64 *b,
                               const u64 *c, u64 *z, hipStream_t s)
 {
+    KernelTimer timer(SPIN_KERNEL_BEAVER_MUL, s);
     for_party_count(n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
         if (count % 2 == 0) {
@@ -201,6 +205,7 @@ spin_status launch_beaver_mul(int n, size_t count, const u64 *x, const u64 *y, c
 spin_status launch_trunc(int n, size_t count, int f, const u64 *x, const u64 *r, const u64 *r_top,
                          const u64 *r_msb, u64 *out, hipStream_t s)
 {
+    KernelTimer timer(SPIN_KERNEL_TRUNC, s);
     for_party_count(n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
         if (count % 2 == 0) {

@@ -340,6 +340,7 @@ spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s)
     PackArgs pb{a.Y, a.B, packB, a.n, a.batch, a.K, a.N, p.nblkB, p.KT};
     for_party_count(a.n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
+        KernelTimer timer(SPIN_KERNEL_PACK, s);
         dim3 ga((unsigned)(((long)p.nblkA * p.KT + 3) / 4), a.n, a.batch);
         pack_kernel<false, NP><<<ga, 256, 0, s>>>(pa);
         dim3 gb((unsigned)(((long)p.nblkB * p.KT + 3) / 4), a.n, a.batch);
@@ -362,6 +363,7 @@ spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s)
         g.kt0 = kt0;
         g.ktn = p.KT - kt0 < kMaxChunkTiles ? p.KT - kt0 : kMaxChunkTiles;
         g.C = kt0 == 0 ? a.C : a.Z;                      // later chunks accumulate onto Z
+        KernelTimer timer(SPIN_KERNEL_GEMM_LIMB, s);
         kernel<<<(unsigned)total, 256, Shape::lds_bytes, s>>>(g);
     }
     return check_launch("spin_beaver_matmul(limb gemm)");

@@ -101,6 +101,7 @@ spin_status launch_matmul_valu(const MatmulArgs &a, hipStream_t s)
     if (st != SPIN_OK) return st;
     st = launch_open(a.Y, a.B, (size_t)a.batch * a.K * a.N, a.n, F, s);
     if (st != SPIN_OK) return st;
+    KernelTimer timer(SPIN_KERNEL_GEMM_VALU, s);
     dim3 grid((a.N + TN - 1) / TN, (a.M + TM - 1) / TM, a.n * a.batch);
     valu_gemm_kernel<<<grid, 256, 0, s>>>(a.n, a.batch, a.M, a.N, a.K, E, F, a.A, a.B, a.C, a.Z);
     return check_launch("spin_beaver_matmul(valu)");

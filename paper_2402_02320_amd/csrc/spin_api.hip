@@ -3,6 +3,8 @@
 // a machine without a GPU.
 #include <string.h>
 
+#include <vector>
+
 #include "common.hpp"
 
 namespace spin {
@@ -20,6 +22,29 @@ spin_status check_launch(const char *where)
     if (e == hipSuccess) return SPIN_OK;
     note_hip_error(e, where);
     return SPIN_EHIP;
+}
+
+// ---- optional per-kernel event timing ---------------------------------------
+namespace {
+struct TimedLaunch { spin_kernel id; hipEvent_t begin, end; };
+bool g_profile = false;
+std::vector<TimedLaunch> g_timed;
+}  // namespace
+
+KernelTimer::KernelTimer(spin_kernel id_, hipStream_t s) : id(id_), stream(s), begin(nullptr), active(false)
+{
+    if (!g_profile) return;
+    if (hipEventCreate(&begin) != hipSuccess) return;
+    active = hipEventRecord(begin, stream) == hipSuccess;
+    if (!active) (void)hipEventDestroy(begin);
+}
+
+KernelTimer::~KernelTimer()
+{
+    if (!active) return;
+    hipEvent_t end;
+    if (hipEventCreate(&end) == hipSuccess && hipEventRecord(end, stream) == hipSuccess)
+        g_timed.push_back({id, begin, end});
 }
 
 namespace {
@@ -115,6 +140,33 @@ spin_status spin_trunc(int n, size_t count, int f, const uint64_t *x, const uint
     if (f < 1 || f > 61) return SPIN_EINVAL;
     if (count > kMaxCount) return SPIN_ERANGE;
     return launch_trunc(n, count, f, x, r, r_top, r_msb, out, (hipStream_t)stream);
+}
+
+void spin_profile_enable(int on) { g_profile = on != 0; }
+
+void spin_profile_reset(void)
+{
+    for (auto &t : g_timed) { (void)hipEventDestroy(t.begin); (void)hipEventDestroy(t.end); }
+    g_timed.clear();
+}
+
+spin_status spin_profile_read(spin_kernel kernel, double *total_ms, unsigned *launches)
+{
+    if (!total_ms || !launches || kernel < 0 || kernel >= SPIN_KERNEL_COUNT) return SPIN_EINVAL;
+    double sum = 0.0;
+    unsigned cnt = 0;
+    for (auto &t : g_timed) {
+        if (t.id != kernel) continue;
+        hipError_t e = hipEventSynchronize(t.end);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, t.begin, t.end);
+        if (e != hipSuccess) { note_hip_error(e, "spin_profile_read"); return SPIN_EHIP; }
+        sum += ms;
+        ++cnt;
+    }
+    *total_ms = sum;
+    *launches = cnt;
+    return SPIN_OK;
 }
 
 const char *spin_status_string(spin_status status)

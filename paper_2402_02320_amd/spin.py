@@ -41,6 +41,11 @@ def lib():
         L.spin_trunc.argtypes = [i32, sz, i32] + [p] * 5 + [p]
         for name in ("spin_random", "spin_share", "spin_open", "spin_beaver_matmul", "spin_beaver_mul", "spin_trunc"):
             getattr(L, name).restype = i32
+        L.spin_profile_enable.argtypes = [i32]
+        L.spin_profile_enable.restype = None
+        L.spin_profile_reset.restype = None
+        L.spin_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint)]
+        L.spin_profile_read.restype = i32
         L.spin_status_string.argtypes = [i32]
         L.spin_status_string.restype = ctypes.c_char_p
         L.spin_last_hip_error.restype = ctypes.c_char_p
@@ -139,6 +144,25 @@ def trunc(x, r, r_top, r_msb, f, out=None):
     _check(lib().spin_trunc(n, x[0].numel(), f, _dev(x, "x"), _dev(r, "r"), _dev(r_top, "r_top"),
                             _dev(r_msb, "r_msb"), _dev(out, "out"), _stream()))
     return out
+
+
+KERNELS = {"random": 0, "share": 1, "open": 2, "beaver_mul": 3, "trunc": 4, "pack": 5, "gemm_limb": 6,
+           "gemm_valu": 7}
+
+
+def profile_enable(on=True):
+    lib().spin_profile_enable(1 if on else 0)
+
+
+def profile_reset():
+    lib().spin_profile_reset()
+
+
+def profile_read(kernel):
+    """(total milliseconds, launches) of one kernel class since the last reset; waits for the events."""
+    ms, cnt = ctypes.c_double(0.0), ctypes.c_uint(0)
+    _check(lib().spin_profile_read(KERNELS[kernel], ctypes.byref(ms), ctypes.byref(cnt)))
+    return ms.value, cnt.value
 
 
 # Fixed-point encoding of Section 4.1 (host-side convenience for the harness; not part of the C ABI).
