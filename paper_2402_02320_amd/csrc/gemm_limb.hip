@@ -153,19 +153,41 @@ struct GemmArgs {
     int tilesM, tilesN;
 };
 
-template <int WM, int WN, int NSTAGE>
+template <int WM, int WN>
 struct GemmShape {
+    static constexpr int NSTAGE = 3;                             // LDS ring: one stage read, two in flight
     static constexpr int BM = 2 * 32 * WM, BN = 2 * 32 * WN;     // 4 waves as 2 x 2
     static constexpr int FA = BM / 32 * kDigits, FB = BN / 32 * kDigits;
     static constexpr int stage_bytes = (FA + FB) * kFrag;
     static constexpr int lds_bytes = NSTAGE * stage_bytes;
     static constexpr int loads_per_wave = (FA + FB) / 4;
+    static constexpr int frags_per_wave = (WM + WN) * kDigits;   // LDS -> register reads per step
+    static constexpr int mfma_per_step = 36 * WM * WN;
 };
 
-template <int WM, int WN, int NSTAGE>
+// One direct-to-LDS load: 64 lanes x 16 bytes from src + lane*16 to the LDS address lds_dst + lane*16.
+// Issued through inline assembly so that the compiler's LDS-DMA bookkeeping does not serialise the
+// software pipeline; completion is awaited explicitly (wait_loads) before the workgroup barrier.
+__device__ inline void load_fragment_to_lds(const char *src, u32 lds_dst, u32 lane16)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(lane16), "s"(src), "s"(lds_dst) : "memory");
+}
+template <int N> __device__ inline void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
+__device__ inline void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ inline void workgroup_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// Pipeline (per wave; step s covers one 32-deep k-tile of one operand pair):
+//   G(s)  12 direct-to-LDS loads of this wave's share of step s into LDS stage s % 3
+//   R(s)  24 ds_read_b128 of the wave's fragments of step s into registers
+//   M(s)  72 MFMAs of step s
+// Iteration s: [wait G(s+1); barrier]  then M(s) interleaved with R(s+1) and G(s+3).
+// The barrier at the top of iteration s also tells every wave that all R(s) are done, so stage s % 3
+// can be refilled by G(s+3).  Two groups of loads are in flight while a step computes.
+template <int WM, int WN>
 __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
 {
-    using S = GemmShape<WM, WN, NSTAGE>;
+    using S = GemmShape<WM, WN>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
 
     const int lane = threadIdx.x % 64;
@@ -203,26 +225,32 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
     const char *b_first = b_second + (size_t)(1 + party) * slotB;                      // B_i'
 
     const int steps = 2 * g.ktn;
-    auto issue_loads = [&](int step, int stage) {
-        const int second = step >= g.ktn;
-        const int kt = g.kt0 + (second ? step - g.ktn : step);
-        const char *as = second ? a_second : a_first, *bs = second ? b_second : b_first;
-        char *dst = lds + stage * S::stage_bytes;
-#pragma unroll
-        for (int q = 0; q < S::loads_per_wave; ++q) {
-            const int f = q * 4 + wave;                  // fragment index within the stage
-            const char *src;
-            if (f < S::FA) {
-                const int blk = tm * (S::BM / 32) + f / kDigits;
-                src = as + ((size_t)blk * g.KT + kt) * (kDigits * kFrag) + (f % kDigits) * kFrag;
-            } else {
-                const int fb = f - S::FA;
-                const int blk = tn * (S::BN / 32) + fb / kDigits;
-                src = bs + ((size_t)blk * g.KT + kt) * (kDigits * kFrag) + (fb % kDigits) * kFrag;
-            }
-            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)(src + lane * 16),
-                                             (void __attribute__((address_space(3))) *)(dst + f * kFrag), 16, 0, 0);
-        }
+    const u32 lds0 = (u32)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
+    const u32 lane16 = lane * 16;
+
+    // Where the loads of one step come from and go to; computed once per step on the scalar unit.
+    // This wave loads fragments f = 4q + wave, q < loads_per_wave: row/column block f / 8 = q / 2 of
+    // the tile and digit f % 8 = 4 (q % 2) + wave, so only q-dependent constants remain per load.
+    struct StepSrc { const char *a, *b; u32 lds; };
+    const size_t blk_stride = (size_t)g.KT * (kDigits * kFrag);
+    const char *tile_a_first = a_first + (size_t)tm * (S::BM / 32) * blk_stride + wave * kFrag;
+    const char *tile_a_second = a_second + (size_t)tm * (S::BM / 32) * blk_stride + wave * kFrag;
+    const char *tile_b_first = b_first + (size_t)tn * (S::BN / 32) * blk_stride + wave * kFrag;
+    const char *tile_b_second = b_second + (size_t)tn * (S::BN / 32) * blk_stride + wave * kFrag;
+    auto step_src = [&](int step) -> StepSrc {
+        const bool second = step >= g.ktn;
+        const size_t kt_off = (size_t)(g.kt0 + (second ? step - g.ktn : step)) * (kDigits * kFrag);
+        StepSrc r;
+        r.a = (second ? tile_a_second : tile_a_first) + kt_off;
+        r.b = (second ? tile_b_second : tile_b_first) + kt_off;
+        r.lds = lds0 + (step % S::NSTAGE) * S::stage_bytes + wave * kFrag;
+        return r;
+    };
+    auto issue_load = [&](const StepSrc &src, int q) {   // q is a compile-time constant after unrolling
+        constexpr int qa = S::FA / 4;                    // loads of left-operand fragments per wave
+        const char *p = q < qa ? src.a + (size_t)(q / 2) * blk_stride + (q % 2) * (4 * kFrag)
+                               : src.b + (size_t)((q - qa) / 2) * blk_stride + ((q - qa) % 2) * (4 * kFrag);
+        load_fragment_to_lds(p, src.lds + q * (4 * kFrag), lane16);
     };
 
     v16i acc[WM][WN][kDigits];
@@ -231,27 +259,51 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
 #pragma unroll
         for (int j = 0; j < WN; ++j)
 #pragma unroll
-            for (int d = 0; d < kDigits; ++d)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][d][r] = 0;
+            for (int d = 0; d < kDigits; ++d) acc[i][j][d] = (v16i)(0);
 
-    issue_loads(0, 0);
-    for (int step = 0; step < steps; ++step) {
-        const int stage = step % NSTAGE;
-        __builtin_amdgcn_s_waitcnt(0);                   // this wave's loads of `step` have landed
-        __syncthreads();                                 // ... and everyone's; stage of step-1 is free
-        const char *sa = lds + stage * S::stage_bytes + (wm * WM * kDigits) * kFrag + lane * 16;
-        const char *sb = lds + stage * S::stage_bytes + (S::FA + wn * WN * kDigits) * kFrag + lane * 16;
-        v4i af[WM][kDigits], bf[WN][kDigits];
+    // fragment registers, double buffered: [buffer][B fragments then A fragments]
+    v4i fr[2][S::frags_per_wave];
+    const char *wave_a = lds + (wm * WM * kDigits) * kFrag + lane16;
+    const char *wave_b = lds + (S::FA + wn * WN * kDigits) * kFrag + lane16;
+    auto read_fragment = [&](int stage, int q) -> v4i {   // q < WN*8: B fragment q; else A fragment q - WN*8
+        const char *p = q < WN * kDigits ? wave_b + q * kFrag : wave_a + (q - WN * kDigits) * kFrag;
+        return *(const v4i *)(p + stage * S::stage_bytes);
+    };
+
+    // prologue: G(0), G(1), G(2); R(0)
+    {
+        const StepSrc s0 = step_src(0), s1 = step_src(1);
 #pragma unroll
-        for (int j = 0; j < WN; ++j)
+        for (int q = 0; q < S::loads_per_wave; ++q) issue_load(s0, q);
 #pragma unroll
-            for (int d = 0; d < kDigits; ++d) bf[j][d] = *(const v4i *)(sb + (j * kDigits + d) * kFrag);
+        for (int q = 0; q < S::loads_per_wave; ++q) issue_load(s1, q);
+    }
+    if (steps > 2) {
+        const StepSrc s2 = step_src(2);
 #pragma unroll
-        for (int i = 0; i < WM; ++i)
+        for (int q = 0; q < S::loads_per_wave; ++q) issue_load(s2, q);
+        wait_loads<2 * S::loads_per_wave>();
+    } else {
+        wait_loads<S::loads_per_wave>();
+    }
+    workgroup_barrier();
 #pragma unroll
-            for (int d = 0; d < kDigits; ++d) af[i][d] = *(const v4i *)(sa + (i * kDigits + d) * kFrag);
-        if (step + 1 < steps) issue_loads(step + 1, (step + 1) % NSTAGE);
+    for (int q = 0; q < S::frags_per_wave; ++q) fr[0][q] = read_fragment(0, q);
+
+    // CUR: register buffer holding step s.  LOAD: step s+3 exists.  NEXT: step s+1 exists.
+    // MORE: step s+2 exists (its loads stay in flight across the wait).
+    auto iteration = [&](auto cur_c, auto load_c, auto next_c, auto more_c, int s) {
+        constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1;
+        constexpr bool LOAD = decltype(load_c)::value, NEXT = decltype(next_c)::value, MORE = decltype(more_c)::value;
+        if (NEXT) {
+            if (MORE) wait_loads<S::loads_per_wave>(); else wait_loads<0>();
+        }
+        wait_lds();
+        workgroup_barrier();
+        const int next_stage = (s + 1) % S::NSTAGE;
+        StepSrc src = {nullptr, nullptr, 0};
+        if (LOAD) src = step_src(s + 3);
+        int slot = 0;
 #pragma unroll
         for (int da = 0; da < kDigits; ++da)
 #pragma unroll
@@ -259,10 +311,46 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
 #pragma unroll
                 for (int i = 0; i < WM; ++i)
 #pragma unroll
-                    for (int j = 0; j < WN; ++j)
-                        acc[i][j][da + db] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i][da], bf[j][db],
-                                                                                  acc[i][j][da + db], 0, 0, 0);
+                    for (int j = 0; j < WN; ++j) {
+                        acc[i][j][da + db] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                            fr[cur][WN * kDigits + i * kDigits + da], fr[cur][j * kDigits + db], acc[i][j][da + db],
+                            0, 0, 0);
+                        // The next step's LDS reads go between the MFMAs of the first two thirds of the
+                        // step (done long before the next barrier), the global loads of step s+3 into the
+                        // last third.  sched_barrier pins this order: left alone, the scheduler sinks each
+                        // read next to its first use and the MFMA pipe then waits out the LDS latency.
+                        constexpr int rd_every = (S::mfma_per_step * 2 / 3) / S::frags_per_wave;
+                        constexpr int ld_first = rd_every * S::frags_per_wave;
+                        constexpr int ld_every = (S::mfma_per_step - ld_first) / S::loads_per_wave;
+                        static_assert(rd_every >= 1 && ld_every >= 1, "tile too small for this interleave");
+                        if (NEXT && slot % rd_every == 0 && slot / rd_every < S::frags_per_wave) {
+                            fr[nxt][slot / rd_every] = read_fragment(next_stage, slot / rd_every);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        if (LOAD && slot >= ld_first && (slot - ld_first) % ld_every == 0 &&
+                            (slot - ld_first) / ld_every < S::loads_per_wave) {
+                            issue_load(src, (slot - ld_first) / ld_every);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        ++slot;
+                    }
+    };
+    using T = std::true_type;
+    using F = std::false_type;
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
+    int s = 0;
+    for (; s + 4 < steps; s += 2) {                       // steps is even; both halves have all neighbours
+        iteration(B0(), T(), T(), T(), s);
+        iteration(B1(), T(), T(), T(), s + 1);
     }
+    if (steps >= 4) {
+        iteration(B0(), T(), T(), T(), s);                // s = steps-4: loads the last step
+        iteration(B1(), F(), T(), T(), s + 1);
+        s += 2;
+    }
+    iteration(B0(), F(), T(), F(), s);                    // s = steps-2
+    iteration(B1(), F(), F(), F(), s + 1);                // s = steps-1
 
     // recombine the diagonals and add C_i
     const size_t mat = (size_t)g.M * g.N;
@@ -286,8 +374,8 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
 }
 
 // ------------------------------------------------------------------ host ---
-constexpr int kWM = 2, kWN = 1, kStages = 2;
-using Shape = GemmShape<kWM, kWN, kStages>;
+constexpr int kWM = 2, kWN = 1;
+using Shape = GemmShape<kWM, kWN>;
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
@@ -350,7 +438,7 @@ spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s)
     if (st != SPIN_OK) return st;
 
     static bool attr_set = false;
-    auto kernel = limb_gemm_kernel<kWM, kWN, kStages>;
+    auto kernel = limb_gemm_kernel<kWM, kWN>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            Shape::lds_bytes);
