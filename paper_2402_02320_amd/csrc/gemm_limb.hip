@@ -141,6 +141,85 @@ __global__ __launch_bounds__(256) void pack_kernel(PackArgs a)
     }
 }
 
+// Left-side pack with coalesced reads.  In pack_kernel<false> a lane reads 128 contiguous bytes of its
+// own matrix row, so one wave-wide load touches 64 different rows; here a wave reads its 32 x 32 tile
+// as 4 rows x 256 contiguous bytes per load, sums the parties' shares in that layout, and turns the
+// tile through LDS (rows padded to 272 bytes, conflict-free for 16-byte accesses both ways) so that
+// each lane ends up with the 16 consecutive k of one row that a fragment chunk needs.
+template <int NP, bool VEC>
+__global__ __launch_bounds__(256) void pack_left_kernel(PackArgs a)
+{
+    constexpr int kRowBytes = 272;
+    __shared__ __attribute__((aligned(16))) char turn[4][32 * kRowBytes];
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    long tile = (long)blockIdx.x * 4 + wave;                // (blk, kt) pair
+    const bool active = tile < (long)a.nblk * a.KT;
+    if (!active) tile = 0;
+    const int blk = (int)(tile / a.KT), kt = (int)(tile % a.KT);
+    const int b = blockIdx.z;
+    const int M = a.rows, K = a.cols;
+    const size_t mat = (size_t)M * K;
+    const size_t party_stride = (size_t)a.batch * mat;
+    const int kk = kt * 32 + 2 * (lane % 16);               // this lane's two k of every row it loads
+    auto frag = [&](int slot) -> char * {
+        return a.pack + ((((size_t)slot * a.batch + b) * a.nblk + blk) * a.KT + kt) * (kDigits * kFrag) + lane * 16;
+    };
+    auto load2 = [&](const u64 *base, int row) -> u64x2 {  // elements (row, kk) and (row, kk+1), zero outside
+        u64x2 v = {0, 0};
+        if (row < M) {
+            const u64 *p = base + (size_t)row * K + kk;
+            if (VEC) { if (kk < K) v = *(const u64x2 *)p; }
+            else { if (kk < K) v.x = p[0]; if (kk + 1 < K) v.y = p[1]; }
+        }
+        return v;
+    };
+    // lane -> LDS: written as (row 4j + lane/16, k pair lane%16), read back as (row lane%32, k 16*(lane/32)..)
+    char *mine = turn[wave];
+    auto turn_and_store = [&](const u64x2 (&v)[8], char *dst) {
+        __syncthreads();                                    // the previous round's reads are done
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            u64x2 d = {to_digits(v[j].x), to_digits(v[j].y)};
+            *(u64x2 *)(mine + (4 * j + lane / 16) * kRowBytes + (lane % 16) * 16) = d;
+        }
+        __syncthreads();
+        u64 w[16];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            u64x2 d = *(const u64x2 *)(mine + (lane % 32) * kRowBytes + (lane / 32) * 128 + j * 16);
+            w[2 * j] = d.x; w[2 * j + 1] = d.y;
+        }
+        if (active) store_digit_rows(w, dst);
+    };
+
+    if (blockIdx.y == 0) {
+        u64x2 opened[8], first[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { opened[j] = (u64x2)(0); first[j] = (u64x2)(0); }
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            const u64 *v = a.val + (size_t)i * party_stride + (size_t)b * mat;
+            const u64 *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int row = blk * 32 + 4 * j + lane / 16;
+                u64x2 tv = load2(t, row);
+                opened[j] += load2(v, row) - tv;
+                if (i == 0) first[j] = tv;
+            }
+        }
+        turn_and_store(opened, frag(0));
+        turn_and_store(first, frag(1));
+    } else {
+        const int i = blockIdx.y;                           // party 1..n-1 -> slot i+1
+        const u64 *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
+        u64x2 v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = load2(t, blk * 32 + 4 * j + lane / 16);
+        turn_and_store(v, frag(i + 1));
+    }
+}
+
 // ------------------------------------------------------------------ GEMM ---
 struct GemmArgs {
     const char *packA;   // [n+1][batch][nblkA][KT][8][1024]: slot 0 = E, slot 1+i = A_i
@@ -430,7 +509,8 @@ spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s)
         constexpr int NP = decltype(np)::value;
         KernelTimer timer(SPIN_KERNEL_PACK, s);
         dim3 ga((unsigned)(((long)p.nblkA * p.KT + 3) / 4), a.n, a.batch);
-        pack_kernel<false, NP><<<ga, 256, 0, s>>>(pa);
+        if (a.K % 2 == 0) pack_left_kernel<NP, true><<<ga, 256, 0, s>>>(pa);   // rows 16-byte aligned
+        else pack_left_kernel<NP, false><<<ga, 256, 0, s>>>(pa);
         dim3 gb((unsigned)(((long)p.nblkB * p.KT + 3) / 4), a.n, a.batch);
         pack_kernel<true, NP><<<gb, 256, 0, s>>>(pb);
     });
