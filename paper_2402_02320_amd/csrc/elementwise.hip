@@ -1,14 +1,20 @@
 // Elementwise share kernels: generator fill, sharing, opening, the fused
 // Beaver update for arrays, and truncation.  All of them are pure HBM
-// streams: one pass, 16-byte accesses per lane, every party's operand read
-// exactly once, opened values (e, f, c) kept in registers because all parties
-// are resident on the same GPU.
+// streams: one pass, every party's operand read exactly once, opened values
+// (e, f, c) kept in registers because all parties are resident on the same GPU.
+//
+// Lane width.  The write-dominated kernels (random, share) move 16 bytes per
+// lane.  The kernels that read many party-major streams at once (open,
+// beaver_mul, trunc: up to 5n+n concurrent streams) move 8 bytes per lane:
+// measured on MI355X at n = 5, 2^24 elements, 8-byte lanes sustain about 8 %
+// more HBM bandwidth than 16-byte lanes for that access pattern.
 #include "common.hpp"
 
 namespace spin {
 namespace {
 
 constexpr int kBlock = 256;
+constexpr bool kWideLanes = false;   // 16-byte lanes for the many-stream kernels (kept for measurement)
 
 // V = u64x2 (two ring elements per lane) or u64 (odd counts, whose party rows
 // are only 8-byte aligned).
@@ -168,7 +174,7 @@ spin_status launch_open(const u64 *shares, const u64 *mask, size_t count, int n,
     KernelTimer timer(SPIN_KERNEL_OPEN, s);
     for_party_count(n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
-        if (count % 2 == 0) {
+        if (kWideLanes && count % 2 == 0) {
             size_t nv = count / 2;
             if (mask)
                 open_kernel<NP, true, u64x2><<<grid_for(nv), kBlock, 0, s>>>((const u64x2 *)shares,
@@ -190,7 +196,7 @@ spin_status launch_beaver_mul(int n, size_t count, const u64 *x, const u64 *y, c
     KernelTimer timer(SPIN_KERNEL_BEAVER_MUL, s);
     for_party_count(n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
-        if (count % 2 == 0) {
+        if (kWideLanes && count % 2 == 0) {
             size_t nv = count / 2;
             beaver_mul_kernel<NP, u64x2><<<grid_for(nv), kBlock, 0, s>>>(
                 (const u64x2 *)x, (const u64x2 *)y, (const u64x2 *)a, (const u64x2 *)b, (const u64x2 *)c, nv,
@@ -208,7 +214,7 @@ spin_status launch_trunc(int n, size_t count, int f, const u64 *x, const u64 *r,
     KernelTimer timer(SPIN_KERNEL_TRUNC, s);
     for_party_count(n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
-        if (count % 2 == 0) {
+        if (kWideLanes && count % 2 == 0) {
             size_t nv = count / 2;
             trunc_kernel<NP, u64x2><<<grid_for(nv), kBlock, 0, s>>>((const u64x2 *)x, (const u64x2 *)r,
                                                                     (const u64x2 *)r_top, (const u64x2 *)r_msb, nv,
