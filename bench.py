@@ -149,6 +149,12 @@ def main():
         spin.beaver_mul(T, w, ea, eb, ec, out=V)
         spin.trunc(V, r2[0], r2[1], r2[2], f, out=V)
 
+    # one plain copy of known size (open of a single share: out[k] = shares[0][k]); the HBM byte counters
+    # of a profiler run are calibrated against what they read for this launch (1 GiB in, 1 GiB out)
+    calib = torch.empty((1, 1 << 27), dtype=torch.int64, device="cuda").fill_(3)
+    calib_out = spin.open(calib)
+    del calib, calib_out
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
