@@ -110,12 +110,14 @@ def main():
     A = party_random(szA, S["A"], (batch, M, K))
     B = party_random(szB, S["B"], (batch, K, N))
     ws_bytes = spin.beaver_matmul_workspace_bytes(n, batch, M, N, K, path)
-    ws1 = torch.empty(spin.beaver_matmul_workspace_bytes(1, batch, M, N, K, path), dtype=torch.uint8, device="cuda")
-    # dealer: C = (sum A_i).(sum B_i) through the library's own ring GEMM (one party, zero triple), then shared
+    # dealer: C = (sum A_i).(sum B_i) through the library's own ring GEMM (one party, zero triple), then shared.
+    # It runs on the VALU path so that every limb_gemm_kernel launch a profiler sees belongs to the workload.
+    ws1 = torch.empty(spin.beaver_matmul_workspace_bytes(1, batch, M, N, K, spin.VALU), dtype=torch.uint8,
+                      device="cuda")
     a_open, b_open = spin.open(A)[None], spin.open(B)[None]
     zA, zB, zC = torch.zeros_like(a_open), torch.zeros_like(b_open), torch.zeros((1, batch, M, N), dtype=torch.int64,
                                                                                 device="cuda")
-    c_plain = spin.beaver_matmul(a_open, b_open, zA, zB, zC, path=path, workspace=ws1)
+    c_plain = spin.beaver_matmul(a_open, b_open, zA, zB, zC, path=spin.VALU, workspace=ws1)
     C = spin.share(c_plain[0], n, c.seed, S["C"])
     del a_open, b_open, zA, zB, zC, c_plain, ws1
 

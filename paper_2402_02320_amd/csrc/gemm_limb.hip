@@ -14,8 +14,8 @@
 // dimension into chunks of at most kMaxChunkTiles k-tiles per operand pair.
 //
 // Two kernels:
-//  pack_kernel   opens E (or F), converts E/A_i (or F/B_i') to digits and
-//                stores them as 1 KiB MFMA fragments: [slot][batch][blk][kt]
+//  pack_left/right_kernel  open E (or F), convert E/A_i (or F/B_i') to digits and
+//                store them as 1 KiB MFMA fragments: [slot][batch][blk][kt]
 //                [digit][lane*16 + j] = digit of element (blk*32 + lane%32,
 //                kt*32 + 16*(lane/32) + j).  Zero padded to whole tiles.
 //  limb_gemm_kernel  per party: Z_i = C_i + [E | A_i] . [B_i' ; F], fragments
@@ -78,74 +78,70 @@ struct PackArgs {
     int nblk, KT;       // blocks of 32 along the non-contracted axis; k-tiles of 32
 };
 
-// BSIDE = false: source is M x K (left operands); a fragment row is a matrix row.
-// BSIDE = true : source is K x N (right operands); a fragment row is a matrix column.
-// blockIdx.y = 0 opens sum_i (val_i - tri_i) into slot 0 and, having party 0's
-// triple share in registers anyway, writes it to slot 1 (left side: A_0; right
-// side: B_0 + F, which folds the public E.F into party 0's first product).
-// blockIdx.y = i >= 1 converts party i's triple share into slot i+1.
-template <bool BSIDE, int NP>
-__global__ __launch_bounds__(256) void pack_kernel(PackArgs a)
+// Both pack kernels make one pass over the 2n share streams of their side: every party's value and
+// triple share is read exactly once; the opened matrix (E or F) accumulates in registers while each
+// triple share is converted and stored as it arrives.  Slots: 0 = opened, 1 + i = party i's triple
+// share (left side A_i; right side B_i, and for party 0 B_0 + F, which folds the public E.F term
+// into party 0's first product).  One wave handles one 32 x 32 tile (blk, kt); blockIdx.z = batch.
+
+// Right side: source K x N row-major, a fragment row is a matrix column, so the 16 consecutive k a
+// lane needs are 16 strided loads whose lanes run along contiguous columns (256-byte segments).
+template <int NP>
+__global__ __launch_bounds__(256) void pack_right_kernel(PackArgs a)
 {
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-    const long tile = (long)blockIdx.x * 4 + wave;          // (blk, kt) pair
+    const long tile = (long)blockIdx.x * 4 + wave;
     if (tile >= (long)a.nblk * a.KT) return;
     const int blk = (int)(tile / a.KT), kt = (int)(tile % a.KT);
     const int b = blockIdx.z;
-    const int rc = blk * 32 + (lane % 32);                  // row (left) / column (right) in the matrix
+    const int K = a.rows, N = a.cols;
+    const int col = blk * 32 + (lane % 32);
     const int k0 = kt * 32 + 16 * (lane / 32);
-    const int K = BSIDE ? a.rows : a.cols;
-    const int RC = BSIDE ? a.cols : a.rows;
-    const size_t mat = (size_t)a.rows * a.cols;
+    const size_t mat = (size_t)K * N;
     const size_t party_stride = (size_t)a.batch * mat;
-
-    auto elem = [&](int j) -> size_t {
-        return BSIDE ? (size_t)(k0 + j) * a.cols + rc : (size_t)rc * a.cols + (k0 + j);
-    };
     auto frag = [&](int slot) -> char * {
         return a.pack + ((((size_t)slot * a.batch + b) * a.nblk + blk) * a.KT + kt) * (kDigits * kFrag) + lane * 16;
     };
-    const bool rc_ok = rc < RC;
-
-    if (blockIdx.y == 0) {
-        u64 opened[16], first[16];
+    u64 opened[16], first[16];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) { opened[j] = 0; first[j] = 0; }
+    for (int j = 0; j < 16; ++j) { opened[j] = 0; first[j] = 0; }
 #pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            const u64 *v = a.val + (size_t)i * party_stride + (size_t)b * mat;
-            const u64 *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
+    for (int i = 0; i < NP; ++i) {
+        const u64 *v = a.val + (size_t)i * party_stride + (size_t)b * mat;
+        const u64 *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
+        u64 tv[16];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                if (rc_ok && k0 + j < K) {
-                    u64 tv = t[elem(j)];
-                    opened[j] += v[elem(j)] - tv;
-                    if (i == 0) first[j] = tv;
-                }
+        for (int j = 0; j < 16; ++j) {
+            tv[j] = 0;
+            if (col < N && k0 + j < K) {
+                const size_t e = (size_t)(k0 + j) * N + col;
+                tv[j] = t[e];
+                opened[j] += v[e] - tv[j];
             }
         }
-        u64 w[16];
+        if (i == 0) {
 #pragma unroll
-        for (int j = 0; j < 16; ++j) w[j] = to_digits(opened[j]);
-        store_digit_rows(w, frag(0));
+            for (int j = 0; j < 16; ++j) first[j] = tv[j];
+        } else {
 #pragma unroll
-        for (int j = 0; j < 16; ++j) w[j] = to_digits(BSIDE ? first[j] + opened[j] : first[j]);
-        store_digit_rows(w, frag(1));
-    } else {
-        const int i = blockIdx.y;                           // party 1..n-1 -> slot i+1
-        const u64 *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
-        u64 w[16];
-#pragma unroll
-        for (int j = 0; j < 16; ++j) w[j] = to_digits((rc_ok && k0 + j < K) ? t[elem(j)] : 0);
-        store_digit_rows(w, frag(i + 1));
+            for (int j = 0; j < 16; ++j) tv[j] = to_digits(tv[j]);
+            store_digit_rows(tv, frag(i + 1));
+        }
     }
+    u64 w[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) w[j] = to_digits(opened[j]);
+    store_digit_rows(w, frag(0));
+#pragma unroll
+    for (int j = 0; j < 16; ++j) w[j] = to_digits(first[j] + opened[j]);
+    store_digit_rows(w, frag(1));
 }
 
-// Left-side pack with coalesced reads.  In pack_kernel<false> a lane reads 128 contiguous bytes of its
-// own matrix row, so one wave-wide load touches 64 different rows; here a wave reads its 32 x 32 tile
-// as 4 rows x 256 contiguous bytes per load, sums the parties' shares in that layout, and turns the
-// tile through LDS (rows padded to 272 bytes, conflict-free for 16-byte accesses both ways) so that
-// each lane ends up with the 16 consecutive k of one row that a fragment chunk needs.
+// Left side: source M x K row-major, a fragment row is a matrix row.  Reading 16 consecutive k per
+// lane directly would make every wave-wide load touch 64 different rows; instead a wave reads its
+// tile as 4 rows x 256 contiguous bytes per load, sums the parties' shares in that layout, and turns
+// each 32 x 32 tile through LDS (rows padded to 272 bytes, conflict-free for 16-byte accesses both
+// ways) so that each lane ends up with the 16 consecutive k of one row that a fragment chunk needs.
 template <int NP, bool VEC>
 __global__ __launch_bounds__(256) void pack_left_kernel(PackArgs a)
 {
@@ -192,32 +188,29 @@ __global__ __launch_bounds__(256) void pack_left_kernel(PackArgs a)
         if (active) store_digit_rows(w, dst);
     };
 
-    if (blockIdx.y == 0) {
-        u64x2 opened[8], first[8];
+    u64x2 opened[8], first[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { opened[j] = (u64x2)(0); first[j] = (u64x2)(0); }
+    for (int j = 0; j < 8; ++j) { opened[j] = (u64x2)(0); first[j] = (u64x2)(0); }
 #pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            const u64 *v = a.val + (size_t)i * party_stride + (size_t)b * mat;
-            const u64 *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int row = blk * 32 + 4 * j + lane / 16;
-                u64x2 tv = load2(t, row);
-                opened[j] += load2(v, row) - tv;
-                if (i == 0) first[j] = tv;
-            }
-        }
-        turn_and_store(opened, frag(0));
-        turn_and_store(first, frag(1));
-    } else {
-        const int i = blockIdx.y;                           // party 1..n-1 -> slot i+1
+    for (int i = 0; i < NP; ++i) {
+        const u64 *v = a.val + (size_t)i * party_stride + (size_t)b * mat;
         const u64 *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
-        u64x2 v[8];
+        u64x2 tv[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = load2(t, blk * 32 + 4 * j + lane / 16);
-        turn_and_store(v, frag(i + 1));
+        for (int j = 0; j < 8; ++j) {
+            const int row = blk * 32 + 4 * j + lane / 16;
+            tv[j] = load2(t, row);
+            opened[j] += load2(v, row) - tv[j];
+        }
+        if (i == 0) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) first[j] = tv[j];
+        } else {
+            turn_and_store(tv, frag(i + 1));
+        }
     }
+    turn_and_store(opened, frag(0));
+    turn_and_store(first, frag(1));
 }
 
 // ------------------------------------------------------------------ GEMM ---
@@ -508,11 +501,11 @@ spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s)
     for_party_count(a.n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
         KernelTimer timer(SPIN_KERNEL_PACK, s);
-        dim3 ga((unsigned)(((long)p.nblkA * p.KT + 3) / 4), a.n, a.batch);
+        dim3 ga((unsigned)(((long)p.nblkA * p.KT + 3) / 4), 1, a.batch);
         if (a.K % 2 == 0) pack_left_kernel<NP, true><<<ga, 256, 0, s>>>(pa);   // rows 16-byte aligned
         else pack_left_kernel<NP, false><<<ga, 256, 0, s>>>(pa);
-        dim3 gb((unsigned)(((long)p.nblkB * p.KT + 3) / 4), a.n, a.batch);
-        pack_kernel<true, NP><<<gb, 256, 0, s>>>(pb);
+        dim3 gb((unsigned)(((long)p.nblkB * p.KT + 3) / 4), 1, a.batch);
+        pack_right_kernel<NP><<<gb, 256, 0, s>>>(pb);
     });
     spin_status st = check_launch("spin_beaver_matmul(pack)");
     if (st != SPIN_OK) return st;
