@@ -39,6 +39,21 @@ def parse():
     return ap.parse_args()
 
 
+def measured_traffic(kernel, cfg):
+    """HBM-side bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE and WRITE_SIZE
+    passes, calibrated against a plain copy), or None where no summary covers this kernel and workload."""
+    path = os.path.join(ROOT, "profiles", "config%d_step_hbm_traffic.txt" % cfg)
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 4 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel \
+                    and parts[2] == "config%d" % cfg:
+                return int(parts[3])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg, target_s):
     """The oracle, as it stands, on a bounded row sample of the same workload."""
     import oracle
@@ -182,13 +197,15 @@ def main():
         ops_per_launch = ring_macs * INT8_OPS_PER_RING_MAC / launches_per_step
         achieved = ops_per_launch / (gemm_avg_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "limb_gemm_kernel", "achieved": achieved, "peak": PEAK_INT8_TOPS,
-                    "unit": "TOP/s", "frac": achieved / PEAK_INT8_TOPS, "traffic": None,
+                    "unit": "TOP/s", "frac": achieved / PEAK_INT8_TOPS,
+                    "traffic": measured_traffic("limb_gemm_kernel", args.config),
                     "avg_launch_ms": gemm_avg_ms, "launches_per_step": launches_per_step,
                     "ring_mac_per_s": ring_macs / launches_per_step / (gemm_avg_ms * 1e-3)}
     else:
-        # 64-bit multiply-add on the vector ALU: 256 CUs x 64 lanes x 4 SIMDs at 2.4 GHz; a ring MAC costs one
-        # v_mad_u64_u32 and two v_mul_lo_u32 (quarter rate each) plus two adds = 14 issue cycles per lane
-        peak = 256 * 4 * 16 * 2.4e9 / 14 / 1e12
+        # 64-bit multiply-add on the vector ALU: 256 CUs x 4 SIMDs x 16 lanes per clock at 2.4 GHz; the compiled
+        # inner loop spends four VALU instructions per ring MAC (v_mad_u64_u32, 2 x v_mul_lo_u32, v_add3_u32),
+        # each taken at full rate
+        peak = 256 * 4 * 16 * 2.4e9 / 4 / 1e12
         achieved = ring_macs / launches_per_step / (gemm_avg_ms * 1e-3) / 1e12
         roofline = {"bound": "alu", "kernel": "valu_gemm_kernel", "achieved": achieved, "peak": peak,
                     "unit": "T ring MAC/s", "frac": achieved / peak, "traffic": None, "avg_launch_ms": gemm_avg_ms,
