@@ -1,0 +1,95 @@
+"""Attention-shaped composition of the two hot-path calls (Sections 7.3 and 7.4): the last Softmax
+multiplication E * R folded into V, (E * R) @ V = E @ (R * V), with the matrix products batched over
+heads.  Shapes: LeViT-256's D1 = D2 = 196, D3 = 64 and the original attention's 512 / 64.  Every GPU
+call is compared bit for bit with the oracle; the ring identity is checked without the intermediate
+truncations and the decoded results of both orders against float64."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2402_02320_amd import spin
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int64)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy().view(np.uint64)
+
+
+def shared(x, n, f, seed, stream):
+    return oracle.share(oracle.encode(x, f), n, seed, stream)
+
+
+def mul_both(x, y, n, seed):
+    """Elementwise Beaver mul on GPU and oracle; asserts equality, returns (gpu tensor, oracle array)."""
+    count = x[0].size
+    a, b, c = oracle.dealer_mul(n, count, seed=seed)
+    zo = oracle.beaver_mul(x.reshape(n, -1), y.reshape(n, -1), a, b, c)
+    zd = spin.beaver_mul(dev(x.reshape(n, -1)), dev(y.reshape(n, -1)), dev(a), dev(b), dev(c))
+    assert (host(zd) == zo).all()
+    return zd, zo
+
+
+def trunc_both(zd, zo, n, f, seed):
+    r, rt, rm = oracle.trunc_dealer(n, zo[0].size, f, seed=seed)
+    to = oracle.trunc(zo.reshape(n, -1), r, rt, rm, f)
+    td = spin.trunc(zd.view(n, -1), dev(r), dev(rt), dev(rm), f)
+    assert (host(td) == to).all()
+    return td, to
+
+
+def matmul_both(X, Y, n, seed, path):
+    _, batch, M, K = X.shape
+    N = Y.shape[3]
+    A, B, C = oracle.dealer_matmul(n, batch, M, N, K, seed=seed)
+    zo = oracle.beaver_matmul(X, Y, A, B, C)
+    zd = spin.beaver_matmul(dev(X), dev(Y), dev(A), dev(B), dev(C), path=path)
+    assert (host(zd) == zo).all()
+    return zd, zo
+
+
+@pytest.mark.parametrize("n,heads,D1,D3", [(3, 4, 196, 64), (2, 2, 512, 64)])
+@pytest.mark.parametrize("path", [pytest.param(spin.LIMB_MFMA, id="limb"), pytest.param(spin.VALU, id="valu")])
+def test_downsized_batch_multiplication(n, heads, D1, D3, path):
+    f, D2 = 14, D1                                       # the paper runs attention at precision 14 (Section 7.2)
+    rng = np.random.default_rng(D1 + n)
+    scores = rng.normal(0, 1, size=(heads, D1, D2))
+    E = np.exp(scores - scores.max(axis=1, keepdims=True))          # Softmax numerators, in (0, 1]
+    R = (1.0 / E.sum(axis=1))[:, :, None]                           # reciprocal of the column sums: 1 x D2 per head
+    V = rng.normal(0, 1, size=(heads, D2, D3))
+    want = np.matmul(E * R.transpose(0, 2, 1), V)
+    seed = 0xA77
+    Es, Vs = shared(E, n, f, seed, 1), shared(V, n, f, seed, 2)
+    Rrow = shared(np.broadcast_to(R.transpose(0, 2, 1), E.shape).copy(), n, f, seed, 3)   # R tiled D1 times
+    Rcol = shared(np.broadcast_to(R, V.shape).copy(), n, f, seed, 3)                      # R tiled D3 times
+
+    # naive order: Mul on D1 x D2 elements, then MatMul
+    sd, so = mul_both(Es, Rrow, n, seed + 1)
+    std, sto = trunc_both(sd, so, n, f, seed + 2)
+    od, oo = matmul_both(sto.reshape(Es.shape), Vs, n, seed + 3, path)
+    otd, _ = trunc_both(od, oo, n, f, seed + 4)
+    naive = oracle.decode(host(spin.open(otd)), f).reshape(want.shape)
+
+    # downsized order: Mul on D2 x D3 elements, then MatMul
+    wd, wo = mul_both(Rcol, Vs, n, seed + 5)
+    wtd, wto = trunc_both(wd, wo, n, f, seed + 6)
+    pd, po = matmul_both(Es, wto.reshape(Vs.shape), n, seed + 7, path)
+    ptd, _ = trunc_both(pd, po, n, f, seed + 8)
+    down = oracle.decode(host(spin.open(ptd)), f).reshape(want.shape)
+
+    bound = 2.0 ** -f * (D2 + 2) * 2
+    assert np.abs(naive - want).max() <= bound
+    assert np.abs(down - want).max() <= bound
+
+    # the identity itself, exact in the ring when the intermediate truncations are left out (precision 3f)
+    lhs = matmul_both(so.reshape(Es.shape), Vs, n, seed + 9, path)[1]
+    rhs = matmul_both(Es, wo.reshape(Vs.shape), n, seed + 10, path)[1]
+    assert (oracle.open_(lhs) == oracle.open_(rhs)).all()
+    assert np.abs(oracle.decode(oracle.open_(lhs), 3 * f) - want).max() <= 2.0 ** -f * (D2 + 2) * 2
+    # and the sizes the paper quotes: the elementwise product shrinks by D1 / D3
+    assert so[0].size // wo[0].size == D1 // D3
