@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--path", default="limb", choices=["limb", "valu"])
+    ap.add_argument("--workload", default="matmul", choices=["matmul", "poly"],
+                    help="matmul: the Beaver-matmul hot path (the benchmark); poly: completed-square polynomial "
+                         "evaluation (Section 7.2 Eq. (4)) on the configuration's vector length")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
@@ -90,6 +93,64 @@ def cpu_baseline(cfg, target_s):
                       "%.3g ring MACs executed, %.3g credited as n*2*rows*N*K)" % (cfg, nrows, M, t, macs, credited)}
 
 
+def bench_poly(args):
+    """Side workload: f1' (completed square, two Beaver multiplications, fused (p+6)-bit truncation) on a vector."""
+    import torch
+    from paper_2402_02320_amd import poly, spin, workloads
+    c = workloads.CONFIGS[args.config]
+    n, p = c.n, 14
+    count = c.vec if c.vec else c.gemms[0].batch * c.gemms[0].M * c.gemms[0].N
+    t3, t2, t1, t0 = 0.96074360, 6.15066406, 24.02000383, 23.85013773      # Appendix B, f1
+    z = torch.rand(count, dtype=torch.float64, device="cuda")
+    x = spin.share(spin.encode(z, p), n, c.seed, 1)
+
+    def party_random(stream):
+        return torch.stack([spin.random(count, c.seed, stream, i) for i in range(n)])
+
+    def triple(s0):
+        a, b = party_random(s0), party_random(s0 + 1)
+        return a, b, spin.share(spin.open(a) * spin.open(b), n, c.seed, s0 + 2)
+
+    def trunc_tuple(f, s0):
+        r_sh = party_random(s0)
+        r = spin.open(r_sh)
+        return r_sh, spin.share((r >> f) & ((1 << (63 - f)) - 1), n, c.seed, s0 + 1), \
+            spin.share((r >> 63) & 1, n, c.seed, s0 + 2)
+    triples = [triple(20), triple(30)]
+    tuples = [trunc_tuple(p, 40), trunc_tuple(p + 6, 50)]
+
+    def step():
+        return poly.evaluate_completed_square(x, -6, t3, t2, t1, t0, p, triples, tuples)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    spin.profile_reset()
+    spin.profile_enable(True)
+    t_begin = time.perf_counter()
+    for _ in range(args.steps):
+        y = step()
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    spin.profile_enable(False)
+    ms = (t_end - t_begin) * 1e3 / args.steps
+    err = float((spin.decode(spin.open(y), p) * (0.01353417 / 2.0 ** -6) - torch.exp2(z)).abs().max())
+    el = 8.0 * count
+    # per step: lincomb (x+t3): 2n; mul: 6n (u read twice counts once: 5n+... u,u,a,b,c in, out) ; trunc 5n;
+    # lincomb (+t2) 2n; mul 6n; lincomb+trunc (2 terms + tuple): 6n  -- element-sized transfers per party
+    alg = {"lincomb": (2 * n + 2 * n + 6 * n) * el / 3, "beaver_mul": 5 * n * el, "trunc": 5 * n * el}
+    kernels = {}
+    for k, b in alg.items():
+        tot, cnt = spin.profile_read(k)
+        if cnt:
+            kernels[k] = {"GB/s": b / (tot / cnt * 1e-3) / 1e9, "avg_ms": tot / cnt, "launches_per_step": cnt / args.steps}
+    spin.profile_reset()
+    print(json.dumps({"metric": "completed-square polynomial evaluations/s (side workload)", "value": count / (ms * 1e-3),
+                      "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+                      "higher_is_better": True, "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+                      "config": {"workload": "f1' of Section 7.2 Eq. (4) on %d elements, %d parties, p=14" % (count, n)},
+                      "max_abs_error_vs_2^z": err, "stream_kernels": kernels}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -105,6 +166,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.workload == "poly":
+        return bench_poly(args)
     c = workloads.CONFIGS[args.config]
     g = c.gemms[0]
     n, f = c.n, c.f

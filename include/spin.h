@@ -117,6 +117,22 @@ spin_status spin_trunc(int n, size_t count, int f, const uint64_t *x,
                        const uint64_t *r, const uint64_t *r_top, const uint64_t *r_msb,
                        uint64_t *out, spin_stream stream);
 
+/* Public-coefficient linear combination followed by one truncation: the local
+ * part of Scale and Add (Section 4.3) and the single deferred truncation of
+ * polynomial evaluation (Section 4.4, Polynomial evaluation; the fused
+ * (p+6)-bit truncation of Section 7.2, Eq. (4)):
+ *     y_i   = sum_j coef[j] * in[j]_i  +  [i=0] constant          (local)
+ *     out   = f > 0 ? Truncate(y, f) : y                           (as spin_trunc)
+ * in:   HOST array of `terms` DEVICE pointers, each a [n][count] share tensor;
+ * coef: HOST array of `terms` public ring coefficients; 1 <= terms <= SPIN_MAX_TERMS.
+ * r, r_top, r_msb: truncation tuple as in spin_trunc (ignored, may be NULL,
+ * when f = 0).  out: [n][count], may alias any input.  0 <= f <= 61.          */
+#define SPIN_MAX_TERMS 8
+spin_status spin_lincomb_trunc(int n, size_t count, int terms, const uint64_t *const *in,
+                               const uint64_t *coef, uint64_t constant, int f,
+                               const uint64_t *r, const uint64_t *r_top, const uint64_t *r_msb,
+                               uint64_t *out, spin_stream stream);
+
 /* Per-kernel timing for benchmarks (measurement aid, not part of the protocol).
  * While enabled, every kernel the library launches is bracketed by a pair of
  * HIP events recorded on the caller's stream; events are created on demand
@@ -133,7 +149,8 @@ typedef enum {
     SPIN_KERNEL_PACK = 5,       /* open + digit split + fragment layout for the limb GEMM */
     SPIN_KERNEL_GEMM_LIMB = 6,
     SPIN_KERNEL_GEMM_VALU = 7,
-    SPIN_KERNEL_COUNT = 8
+    SPIN_KERNEL_LINCOMB = 8,
+    SPIN_KERNEL_COUNT = 9
 } spin_kernel;
 void spin_profile_enable(int on);
 spin_status spin_profile_read(spin_kernel kernel, double *total_ms, unsigned *launches);

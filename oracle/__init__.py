@@ -56,6 +56,8 @@ def lib():
         L.oracle_trunc.argtypes = [i32, sz, i32, i32] + [p] * 5
         L.oracle_local_shift_trunc.argtypes = [i32, sz, i32, p, p]
         L.oracle_threads.restype = i32
+        L.oracle_lincomb.argtypes = [i32, sz, i32, i32, p, p, u64, p]
+        L.oracle_lincomb.restype = None
         L.oracle_random.argtypes = [p, sz, u64, u64, u64, u64]
         L.oracle_random.restype = None
         for name in ("oracle_encode", "oracle_decode", "oracle_share", "oracle_open",
@@ -218,3 +220,69 @@ def random(count, seed, stream, party, first=0):
     out = np.empty((count,), dtype=np.uint64)
     lib().oracle_random(_ptr(out), count, seed, stream, party, first)
     return out
+
+
+def lincomb(terms, coefs, constant=0, l=64):
+    """out_i = sum_j coefs[j] * terms[j]_i + [i=0] constant (Section 4.3, Addition and Scaling)."""
+    terms = [_u64(t) for t in terms]
+    n = terms[0].shape[0]
+    count = terms[0][0].size
+    assert all(t.shape == terms[0].shape for t in terms) and len(coefs) == len(terms)
+    ptrs = (ctypes.c_void_p * len(terms))(*[t.ctypes.data for t in terms])
+    cf = np.array([int(c) % (1 << 64) for c in coefs], dtype=np.uint64)
+    out = np.empty(terms[0].shape, dtype=np.uint64)
+    lib().oracle_lincomb(n, count, l, len(terms), ptrs, _ptr(cf), int(constant) % (1 << 64), _ptr(out))
+    return out
+
+
+def _enc1(v, p):
+    """[v]_p of one public real (Section 4.1)."""
+    return int(encode(np.array([v]), p)[0])
+
+
+def evaluate_poly(x_sh, coeffs, p, seed, l=64):
+    """Evaluate (Section 4.4, Polynomial evaluation): f(x) = sum_i coeffs[i] x^i with public coefficients.
+
+    The powers x^2 .. x^d are formed one after the other by Mul + Truncate; the terms a_i x^i are
+    scaled without truncation (precision 2p) and summed, a_0 joins at precision 2p, and a single
+    Truncate brings the sum back to precision p.  Triples and truncation tuples are dealt from
+    `seed + step`.  Returns shares of [f(x)]_p."""
+    x_sh = _u64(x_sh)
+    n = x_sh.shape[0]
+    flat = x_sh.reshape(n, -1)
+    count = flat.shape[1]
+    d = len(coeffs) - 1
+    powers = [flat]
+    for i in range(2, d + 1):
+        a, b, c = dealer_mul(n, count, seed + 10 * i, l)
+        prod = beaver_mul(powers[-1], flat, a, b, c, l)
+        r, rt, rm = trunc_dealer(n, count, p, seed + 10 * i + 1, l)
+        powers.append(trunc(prod, r, rt, rm, p, l))
+    total = lincomb(powers, [_enc1(coeffs[i], p) for i in range(1, d + 1)], _enc1(coeffs[0], 2 * p), l)
+    r, rt, rm = trunc_dealer(n, count, p, seed + 1, l)
+    return trunc(total, r, rt, rm, p, l).reshape(x_sh.shape)
+
+
+def evaluate_completed_square(x_sh, k4p_log2, t3, t2, t1, t0, p, seed, l=64):
+    """The completed-square evaluation of a quartic (Section 7.2, Eq. (4)):
+        f'(x) = k4' ((x + t3)^2 + t2)^2 + (k4' t1) x + k4' t0,   k4' = 2^k4p_log2 (a power of two).
+    Two secure multiplications; the factor k4' is not multiplied in but folded into the last
+    truncation, which removes p - k4p_log2 bits instead of p; the linear and constant terms are
+    pre-scaled by 2^-k4p_log2 so that they join that same truncation."""
+    x_sh = _u64(x_sh)
+    n = x_sh.shape[0]
+    flat = x_sh.reshape(n, -1)
+    count = flat.shape[1]
+    shift = -k4p_log2                                   # k4' = 2^-shift
+    k4p = 2.0 ** k4p_log2
+    u = lincomb([flat], [1], _enc1(t3, p), l)                               # x + t3
+    a, b, c = dealer_mul(n, count, seed + 20, l)
+    r, rt, rm = trunc_dealer(n, count, p, seed + 21, l)
+    u2 = trunc(beaver_mul(u, u, a, b, c, l), r, rt, rm, p, l)               # (x + t3)^2 at precision p
+    v = lincomb([u2], [1], _enc1(t2, p), l)                                 # ... + t2
+    a, b, c = dealer_mul(n, count, seed + 22, l)
+    v2 = beaver_mul(v, v, a, b, c, l)                                       # precision 2p, kept
+    # v^2 + 2^shift (k4' t1) x + 2^shift k4' t0, all at precision 2p, then one truncation by p + shift
+    total = lincomb([v2, flat], [1, _enc1(k4p * t1, p) << shift], _enc1(k4p * t0, 2 * p) << shift, l)
+    r, rt, rm = trunc_dealer(n, count, p + shift, seed + 23, l)
+    return trunc(total, r, rt, rm, p + shift, l).reshape(x_sh.shape)

@@ -352,3 +352,21 @@ void oracle_random(u64 *out, size_t count, u64 seed, u64 stream, u64 party, u64 
 {
     for (size_t k = 0; k < count; ++k) out[k] = oracle_rand64(seed, stream, party, first + k);
 }
+
+/* ------------------------------------------------------------------------ */
+/* Local linear combination with public coefficients (Section 4.3: Addition is
+ * share-wise, Scaling multiplies every share by the public k; a public
+ * constant is added by party 0 only):
+ *   out_i = sum_j coef[j] * in[j]_i  +  [i = 0] constant.
+ * in: `terms` pointers to [n][count] share tensors. */
+void oracle_lincomb(int n, size_t count, int l, int terms, const u64 *const *in, const u64 *coef,
+                    u64 constant, u64 *out)
+{
+    u64 mask = ring_mask(l);
+    for (int i = 0; i < n; ++i)
+        for (size_t k = 0; k < count; ++k) {
+            u64 acc = (i == 0) ? constant : 0;
+            for (int j = 0; j < terms; ++j) acc += coef[j] * in[j][(size_t)i * count + k];
+            out[(size_t)i * count + k] = acc & mask;
+        }
+}

@@ -51,6 +51,10 @@ spin_status launch_beaver_mul(int n, size_t count, const u64 *x, const u64 *y, c
 spin_status launch_trunc(int n, size_t count, int f, const u64 *x, const u64 *r, const u64 *r_top,
                          const u64 *r_msb, u64 *out, hipStream_t s);
 
+struct LincombTerms { const u64 *in[SPIN_MAX_TERMS]; u64 coef[SPIN_MAX_TERMS]; int terms; };
+spin_status launch_lincomb_trunc(int n, size_t count, const LincombTerms &t, u64 constant, int f, const u64 *r,
+                                 const u64 *r_top, const u64 *r_msb, u64 *out, hipStream_t s);
+
 struct MatmulArgs {
     int n, batch, M, N, K;
     const u64 *X, *Y, *A, *B, *C;

@@ -126,6 +126,51 @@ __global__ __launch_bounds__(kBlock) void trunc_kernel(const V *x, const V *__re
     }
 }
 
+// y_i = sum_j coef_j in_j,i (+ constant for party 0), then the truncation of trunc_kernel on y when
+// TRUNC (Section 4.3 Addition/Scaling; Section 4.4 Polynomial evaluation: one deferred truncation).
+// The term loop is a run-time loop; every iteration issues one load per party.
+template <int NP, bool TRUNC>
+__global__ __launch_bounds__(kBlock) void lincomb_trunc_kernel(LincombTerms t, u64 constant, const u64 *__restrict__ r,
+                                                              const u64 *__restrict__ r_top,
+                                                              const u64 *__restrict__ r_msb, size_t count, int f,
+                                                              u64 *out)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= count) return;
+    u64 y[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) y[i] = i == 0 ? constant : 0;
+    for (int j = 0; j < t.terms; ++j) {
+        const u64 *src = t.in[j];
+        const u64 cf = t.coef[j];
+#pragma unroll
+        for (int i = 0; i < NP; ++i) y[i] += cf * src[(size_t)i * count + v];
+    }
+    if (!TRUNC) {
+#pragma unroll
+        for (int i = 0; i < NP; ++i) out[(size_t)i * count + v] = y[i];
+        return;
+    }
+    u64 rt[NP], rm[NP];
+    u64 c = (u64)1 << 62;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        size_t o = (size_t)i * count + v;
+        rt[i] = r_top[o]; rm[i] = r_msb[o];
+        c += y[i] + r[o];
+    }
+    const u64 topmask = (((u64)1 << (63 - f)) - 1);
+    u64 c_msb = c >> 63;
+    u64 c_top = (c >> f) & topmask;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        u64 b = rm[i] - 2 * c_msb * rm[i];
+        u64 o = (b << (63 - f)) - rt[i];
+        if (i == 0) o += (c_msb << (63 - f)) + c_top - ((u64)1 << (62 - f));
+        out[(size_t)i * count + v] = o;
+    }
+}
+
 inline unsigned grid_for(size_t nvec) { return (unsigned)((nvec + kBlock - 1) / kBlock); }
 
 // Calls fn(integral_constant<int, n>) for the run-time party count.
@@ -224,6 +269,21 @@ spin_status launch_trunc(int n, size_t count, int f, const u64 *x, const u64 *r,
         }
     });
     return check_launch("spin_trunc");
+}
+
+spin_status launch_lincomb_trunc(int n, size_t count, const LincombTerms &t, u64 constant, int f, const u64 *r,
+                                 const u64 *r_top, const u64 *r_msb, u64 *out, hipStream_t s)
+{
+    KernelTimer timer(SPIN_KERNEL_LINCOMB, s);
+    for_party_count(n, [&](auto np) {
+        constexpr int NP = decltype(np)::value;
+        if (f > 0)
+            lincomb_trunc_kernel<NP, true><<<grid_for(count), kBlock, 0, s>>>(t, constant, r, r_top, r_msb, count, f, out);
+        else
+            lincomb_trunc_kernel<NP, false><<<grid_for(count), kBlock, 0, s>>>(t, constant, nullptr, nullptr, nullptr,
+                                                                              count, 0, out);
+    });
+    return check_launch("spin_lincomb_trunc");
 }
 
 }  // namespace spin

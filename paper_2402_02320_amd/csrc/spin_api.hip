@@ -169,6 +169,25 @@ spin_status spin_profile_read(spin_kernel kernel, double *total_ms, unsigned *la
     return SPIN_OK;
 }
 
+spin_status spin_lincomb_trunc(int n, size_t count, int terms, const uint64_t *const *in, const uint64_t *coef,
+                               uint64_t constant, int f, const uint64_t *r, const uint64_t *r_top,
+                               const uint64_t *r_msb, uint64_t *out, spin_stream stream)
+{
+    if (in == nullptr || coef == nullptr || bad_ptr(out) || bad_n(n) || count == 0) return SPIN_EINVAL;
+    if (terms < 1 || terms > SPIN_MAX_TERMS || f < 0 || f > 61) return SPIN_EINVAL;
+    if (f > 0 && (bad_ptr(r) || bad_ptr(r_top) || bad_ptr(r_msb))) return SPIN_EINVAL;
+    LincombTerms t;
+    t.terms = terms;
+    for (int j = 0; j < SPIN_MAX_TERMS; ++j) { t.in[j] = nullptr; t.coef[j] = 0; }
+    for (int j = 0; j < terms; ++j) {
+        if (bad_ptr(in[j])) return SPIN_EINVAL;
+        t.in[j] = in[j];
+        t.coef[j] = coef[j];
+    }
+    if (count > kMaxCount) return SPIN_ERANGE;
+    return launch_lincomb_trunc(n, count, t, constant, f, r, r_top, r_msb, out, (hipStream_t)stream);
+}
+
 const char *spin_status_string(spin_status status)
 {
     switch (status) {

@@ -39,6 +39,8 @@ def lib():
         L.spin_beaver_matmul_workspace_bytes.restype = sz
         L.spin_beaver_mul.argtypes = [i32, sz] + [p] * 6 + [p]
         L.spin_trunc.argtypes = [i32, sz, i32] + [p] * 5 + [p]
+        L.spin_lincomb_trunc.argtypes = [i32, sz, i32, p, p, u64, i32, p, p, p, p, p]
+        L.spin_lincomb_trunc.restype = i32
         for name in ("spin_random", "spin_share", "spin_open", "spin_beaver_matmul", "spin_beaver_mul", "spin_trunc"):
             getattr(L, name).restype = i32
         L.spin_profile_enable.argtypes = [i32]
@@ -146,8 +148,29 @@ def trunc(x, r, r_top, r_msb, f, out=None):
     return out
 
 
+def lincomb_trunc(terms, coefs, constant=0, f=0, tuple_=None, out=None):
+    """out = Truncate(sum_j coefs[j] * terms[j] + constant, f); f = 0 leaves the sum untruncated."""
+    n = terms[0].shape[0]
+    for t in terms:
+        if t.shape != terms[0].shape:
+            raise SpinError("inconsistent operand shapes")
+    if out is None:
+        out = torch.empty_like(terms[0])
+    ptrs = (ctypes.c_void_p * len(terms))(*[_dev(t, "term") for t in terms])
+    cf = (ctypes.c_uint64 * len(terms))(*[int(c) % (1 << 64) for c in coefs])
+    r = rt = rm = None
+    if f > 0:
+        r, rt, rm = (_dev(t, "tuple") for t in tuple_)
+        for t in tuple_:
+            if t.numel() != terms[0].numel():
+                raise SpinError("truncation tuple must have the shape of the terms")
+    _check(lib().spin_lincomb_trunc(n, terms[0][0].numel(), len(terms), ptrs, cf, int(constant) % (1 << 64), f,
+                                    r, rt, rm, _dev(out, "out"), _stream()))
+    return out
+
+
 KERNELS = {"random": 0, "share": 1, "open": 2, "beaver_mul": 3, "trunc": 4, "pack": 5, "gemm_limb": 6,
-           "gemm_valu": 7}
+           "gemm_valu": 7, "lincomb": 8}
 
 
 def profile_enable(on=True):
