@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "../../include/spin.h"
 
 namespace spin {
@@ -29,6 +31,22 @@ inline u64 stream_key(u64 seed, u64 stream_id, u64 party)
 }
 
 struct PartyKeys { u64 key[SPIN_MAX_PARTIES]; };
+
+// Calls fn(std::integral_constant<int, n>) for the run-time party count, so that kernels can be
+// templated on it (all of a thread's per-party loads are then issued before the first use).
+template <class F> inline void for_party_count(int n, F &&fn)
+{
+    switch (n) {
+    case 1: fn(std::integral_constant<int, 1>()); break;
+    case 2: fn(std::integral_constant<int, 2>()); break;
+    case 3: fn(std::integral_constant<int, 3>()); break;
+    case 4: fn(std::integral_constant<int, 4>()); break;
+    case 5: fn(std::integral_constant<int, 5>()); break;
+    case 6: fn(std::integral_constant<int, 6>()); break;
+    case 7: fn(std::integral_constant<int, 7>()); break;
+    default: fn(std::integral_constant<int, 8>()); break;
+    }
+}
 
 // ---- launch bookkeeping ------------------------------------------------------
 void note_hip_error(hipError_t e, const char *where);

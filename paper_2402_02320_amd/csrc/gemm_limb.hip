@@ -468,20 +468,6 @@ inline Plan make_plan(int n, int batch, int M, int N, int K)
     return p;
 }
 
-template <class F> inline void for_party_count(int n, F &&fn)
-{
-    switch (n) {
-    case 1: fn(std::integral_constant<int, 1>()); break;
-    case 2: fn(std::integral_constant<int, 2>()); break;
-    case 3: fn(std::integral_constant<int, 3>()); break;
-    case 4: fn(std::integral_constant<int, 4>()); break;
-    case 5: fn(std::integral_constant<int, 5>()); break;
-    case 6: fn(std::integral_constant<int, 6>()); break;
-    case 7: fn(std::integral_constant<int, 7>()); break;
-    default: fn(std::integral_constant<int, 8>()); break;
-    }
-}
-
 }  // namespace
 
 size_t limb_workspace_bytes(int n, int batch, int M, int N, int K)
