@@ -300,29 +300,31 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
     const u32 lds0 = (u32)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
     const u32 lane16 = lane * 16;
 
-    // Where the loads of one step come from and go to; computed once per step on the scalar unit.
+    // Load cursor: where the loads of the next step to be fetched come from and go to.  It lives on
+    // the scalar unit and advances by one k-tile per step (no division, no per-load selects); at the
+    // switch from the first operand pair to the second it jumps to the other fragment streams.
     // This wave loads fragments f = 4q + wave, q < loads_per_wave: row/column block f / 8 = q / 2 of
     // the tile and digit f % 8 = 4 (q % 2) + wave, so only q-dependent constants remain per load.
-    struct StepSrc { const char *a, *b; u32 lds; };
     const size_t blk_stride = (size_t)g.KT * (kDigits * kFrag);
-    const char *tile_a_first = a_first + (size_t)tm * (S::BM / 32) * blk_stride + wave * kFrag;
-    const char *tile_a_second = a_second + (size_t)tm * (S::BM / 32) * blk_stride + wave * kFrag;
-    const char *tile_b_first = b_first + (size_t)tn * (S::BN / 32) * blk_stride + wave * kFrag;
-    const char *tile_b_second = b_second + (size_t)tn * (S::BN / 32) * blk_stride + wave * kFrag;
-    auto step_src = [&](int step) -> StepSrc {
-        const bool second = step >= g.ktn;
-        const size_t kt_off = (size_t)(g.kt0 + (second ? step - g.ktn : step)) * (kDigits * kFrag);
-        StepSrc r;
-        r.a = (second ? tile_a_second : tile_a_first) + kt_off;
-        r.b = (second ? tile_b_second : tile_b_first) + kt_off;
-        r.lds = lds0 + (step % S::NSTAGE) * S::stage_bytes + wave * kFrag;
-        return r;
-    };
-    auto issue_load = [&](const StepSrc &src, int q) {   // q is a compile-time constant after unrolling
+    const size_t kt0_off = (size_t)g.kt0 * (kDigits * kFrag) + wave * kFrag;
+    const char *ld_a = a_first + (size_t)tm * (S::BM / 32) * blk_stride + kt0_off;
+    const char *ld_b = b_first + (size_t)tn * (S::BN / 32) * blk_stride + kt0_off;
+    const char *second_a = a_second + (size_t)tm * (S::BM / 32) * blk_stride + kt0_off;
+    const char *second_b = b_second + (size_t)tn * (S::BN / 32) * blk_stride + kt0_off;
+    int ld_left = g.ktn;                                 // steps until the cursor switches operand pair
+    u32 ld_lds = lds0 + wave * kFrag;                    // LDS destination of the cursor's stage
+    const u32 lds_wrap = lds0 + wave * kFrag + (S::NSTAGE - 1) * S::stage_bytes;
+    auto issue_load = [&](int q) {                       // q is a compile-time constant after unrolling
         constexpr int qa = S::FA / 4;                    // loads of left-operand fragments per wave
-        const char *p = q < qa ? src.a + (size_t)(q / 2) * blk_stride + (q % 2) * (4 * kFrag)
-                               : src.b + (size_t)((q - qa) / 2) * blk_stride + ((q - qa) % 2) * (4 * kFrag);
-        load_fragment_to_lds(p, src.lds + q * (4 * kFrag), lane16);
+        const char *p = q < qa ? ld_a + (size_t)(q / 2) * blk_stride + (q % 2) * (4 * kFrag)
+                               : ld_b + (size_t)((q - qa) / 2) * blk_stride + ((q - qa) % 2) * (4 * kFrag);
+        load_fragment_to_lds(p, ld_lds + q * (4 * kFrag), lane16);
+    };
+    auto advance_load_cursor = [&]() {
+        ld_a += kDigits * kFrag;
+        ld_b += kDigits * kFrag;
+        if (--ld_left == 0) { ld_a = second_a; ld_b = second_b; }
+        ld_lds = ld_lds == lds_wrap ? lds_wrap - (S::NSTAGE - 1) * S::stage_bytes : ld_lds + S::stage_bytes;
     };
 
     v16i acc[WM][WN][kDigits];
@@ -333,38 +335,44 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
 #pragma unroll
             for (int d = 0; d < kDigits; ++d) acc[i][j][d] = (v16i)(0);
 
-    // fragment registers, double buffered: [buffer][B fragments then A fragments]
+    // fragment registers, double buffered: [buffer][B fragments then A fragments]; the read cursor
+    // (two LDS pointers of this wave within the stage to be read next) cycles through the stages
     v4i fr[2][S::frags_per_wave];
-    const char *wave_a = lds + (wm * WM * kDigits) * kFrag + lane16;
-    const char *wave_b = lds + (S::FA + wn * WN * kDigits) * kFrag + lane16;
-    auto read_fragment = [&](int stage, int q) -> v4i {   // q < WN*8: B fragment q; else A fragment q - WN*8
-        const char *p = q < WN * kDigits ? wave_b + q * kFrag : wave_a + (q - WN * kDigits) * kFrag;
-        return *(const v4i *)(p + stage * S::stage_bytes);
+    const char *rd_a = lds + (wm * WM * kDigits) * kFrag + lane16;
+    const char *rd_b = lds + (S::FA + wn * WN * kDigits) * kFrag + lane16;
+    const char *rd_wrap = rd_a + (S::NSTAGE - 1) * S::stage_bytes;
+    auto read_fragment = [&](int q) -> v4i {             // q < WN*8: B fragment q; else A fragment q - WN*8
+        return *(const v4i *)(q < WN * kDigits ? rd_b + q * kFrag : rd_a + (q - WN * kDigits) * kFrag);
+    };
+    auto advance_read_cursor = [&]() {
+        const bool wrap = rd_a == rd_wrap;
+        rd_a = wrap ? rd_a - (S::NSTAGE - 1) * S::stage_bytes : rd_a + S::stage_bytes;
+        rd_b = wrap ? rd_b - (S::NSTAGE - 1) * S::stage_bytes : rd_b + S::stage_bytes;
     };
 
     // prologue: G(0), G(1), G(2); R(0)
-    {
-        const StepSrc s0 = step_src(0), s1 = step_src(1);
 #pragma unroll
-        for (int q = 0; q < S::loads_per_wave; ++q) issue_load(s0, q);
+    for (int q = 0; q < S::loads_per_wave; ++q) issue_load(q);
+    advance_load_cursor();
 #pragma unroll
-        for (int q = 0; q < S::loads_per_wave; ++q) issue_load(s1, q);
-    }
+    for (int q = 0; q < S::loads_per_wave; ++q) issue_load(q);
+    advance_load_cursor();
     if (steps > 2) {
-        const StepSrc s2 = step_src(2);
 #pragma unroll
-        for (int q = 0; q < S::loads_per_wave; ++q) issue_load(s2, q);
+        for (int q = 0; q < S::loads_per_wave; ++q) issue_load(q);
+        advance_load_cursor();
         wait_loads<2 * S::loads_per_wave>();
     } else {
         wait_loads<S::loads_per_wave>();
     }
     workgroup_barrier();
 #pragma unroll
-    for (int q = 0; q < S::frags_per_wave; ++q) fr[0][q] = read_fragment(0, q);
+    for (int q = 0; q < S::frags_per_wave; ++q) fr[0][q] = read_fragment(q);
+    advance_read_cursor();
 
-    // CUR: register buffer holding step s.  LOAD: step s+3 exists.  NEXT: step s+1 exists.
-    // MORE: step s+2 exists (its loads stay in flight across the wait).
-    auto iteration = [&](auto cur_c, auto load_c, auto next_c, auto more_c, int s) {
+    // One step.  CUR: register buffer holding this step.  LOAD: the step three ahead exists.
+    // NEXT: the next step exists.  MORE: the step two ahead exists (its loads stay in flight across the wait).
+    auto iteration = [&](auto cur_c, auto load_c, auto next_c, auto more_c) {
         constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1;
         constexpr bool LOAD = decltype(load_c)::value, NEXT = decltype(next_c)::value, MORE = decltype(more_c)::value;
         if (NEXT) {
@@ -372,9 +380,6 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
         }
         wait_lds();
         workgroup_barrier();
-        const int next_stage = (s + 1) % S::NSTAGE;
-        StepSrc src = {nullptr, nullptr, 0};
-        if (LOAD) src = step_src(s + 3);
         int slot = 0;
 #pragma unroll
         for (int da = 0; da < kDigits; ++da)
@@ -388,24 +393,27 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
                             fr[cur][WN * kDigits + i * kDigits + da], fr[cur][j * kDigits + db], acc[i][j][da + db],
                             0, 0, 0);
                         // The next step's LDS reads go between the MFMAs of the first two thirds of the
-                        // step (done long before the next barrier), the global loads of step s+3 into the
-                        // last third.  sched_barrier pins this order: left alone, the scheduler sinks each
-                        // read next to its first use and the MFMA pipe then waits out the LDS latency.
+                        // step (done long before the next barrier), the global loads of the step three
+                        // ahead into the last third.  sched_barrier pins this order: left alone, the
+                        // scheduler sinks each read next to its first use and the MFMA pipe then waits
+                        // out the LDS latency.
                         constexpr int rd_every = (S::mfma_per_step * 2 / 3) / S::frags_per_wave;
                         constexpr int ld_first = rd_every * S::frags_per_wave;
                         constexpr int ld_every = (S::mfma_per_step - ld_first) / S::loads_per_wave;
                         static_assert(rd_every >= 1 && ld_every >= 1, "tile too small for this interleave");
                         if (NEXT && slot % rd_every == 0 && slot / rd_every < S::frags_per_wave) {
-                            fr[nxt][slot / rd_every] = read_fragment(next_stage, slot / rd_every);
+                            fr[nxt][slot / rd_every] = read_fragment(slot / rd_every);
                             __builtin_amdgcn_sched_barrier(0);
                         }
                         if (LOAD && slot >= ld_first && (slot - ld_first) % ld_every == 0 &&
                             (slot - ld_first) / ld_every < S::loads_per_wave) {
-                            issue_load(src, (slot - ld_first) / ld_every);
+                            issue_load((slot - ld_first) / ld_every);
                             __builtin_amdgcn_sched_barrier(0);
                         }
                         ++slot;
                     }
+        if (NEXT) advance_read_cursor();
+        if (LOAD) advance_load_cursor();
     };
     using T = std::true_type;
     using F = std::false_type;
@@ -413,16 +421,15 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
     using B1 = std::integral_constant<int, 1>;
     int s = 0;
     for (; s + 4 < steps; s += 2) {                       // steps is even; both halves have all neighbours
-        iteration(B0(), T(), T(), T(), s);
-        iteration(B1(), T(), T(), T(), s + 1);
+        iteration(B0(), T(), T(), T());
+        iteration(B1(), T(), T(), T());
     }
     if (steps >= 4) {
-        iteration(B0(), T(), T(), T(), s);                // s = steps-4: loads the last step
-        iteration(B1(), F(), T(), T(), s + 1);
-        s += 2;
+        iteration(B0(), T(), T(), T());                   // step steps-4: loads the last step
+        iteration(B1(), F(), T(), T());
     }
-    iteration(B0(), F(), T(), F(), s);                    // s = steps-2
-    iteration(B1(), F(), F(), F(), s + 1);                // s = steps-1
+    iteration(B0(), F(), T(), F());                       // step steps-2
+    iteration(B1(), F(), F(), F());                       // step steps-1
 
     // recombine the diagonals and add C_i
     const size_t mat = (size_t)g.M * g.N;
