@@ -23,6 +23,19 @@
 //                32x32x32 step into 8 diagonal accumulators, recombined once.
 #include "common.hpp"
 
+// Interleave of one k-step of the GEMM (slots = MFMA index within the step, 72 per step for the 64x32
+// wave tile): an LDS read after every RD_EVERY-th MFMA from slot 0, a direct-to-LDS load after every
+// LD_EVERY-th MFMA from slot LD_FIRST.
+#ifndef SPIN_TUNE_RD_EVERY
+#define SPIN_TUNE_RD_EVERY 2
+#endif
+#ifndef SPIN_TUNE_LD_FIRST
+#define SPIN_TUNE_LD_FIRST 13
+#endif
+#ifndef SPIN_TUNE_LD_EVERY
+#define SPIN_TUNE_LD_EVERY 4
+#endif
+
 namespace spin {
 namespace {
 
@@ -392,28 +405,38 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
                         acc[i][j][da + db] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
                             fr[cur][WN * kDigits + i * kDigits + da], fr[cur][j * kDigits + db], acc[i][j][da + db],
                             0, 0, 0);
-                        // The next step's LDS reads go between the MFMAs of the first two thirds of the
-                        // step (done long before the next barrier), the global loads of the step three
-                        // ahead into the last third.  sched_barrier pins this order: left alone, the
+                        // Between the MFMAs: the next step's LDS reads (every rd_every-th slot from the
+                        // start, so they are done long before the next barrier), the global loads of the
+                        // step three ahead (every ld_every-th slot from ld_first), and the two cursor
+                        // updates, so that the last MFMAs of a step and the barrier that follows have no
+                        // scalar work between them.  sched_barrier pins this order: left alone, the
                         // scheduler sinks each read next to its first use and the MFMA pipe then waits
                         // out the LDS latency.
-                        constexpr int rd_every = (S::mfma_per_step * 2 / 3) / S::frags_per_wave;
-                        constexpr int ld_first = rd_every * S::frags_per_wave;
-                        constexpr int ld_every = (S::mfma_per_step - ld_first) / S::loads_per_wave;
-                        static_assert(rd_every >= 1 && ld_every >= 1, "tile too small for this interleave");
-                        if (NEXT && slot % rd_every == 0 && slot / rd_every < S::frags_per_wave) {
+                        constexpr int rd_every = SPIN_TUNE_RD_EVERY;
+                        constexpr int rd_last = rd_every * (S::frags_per_wave - 1);
+                        constexpr int ld_first = SPIN_TUNE_LD_FIRST;
+                        constexpr int ld_every = SPIN_TUNE_LD_EVERY;
+                        constexpr int ld_last = ld_first + ld_every * (S::loads_per_wave - 1);
+                        static_assert(rd_every >= 1 && ld_every >= 1 && ld_last + 1 < S::mfma_per_step &&
+                                      rd_last + 1 < S::mfma_per_step, "tile too small for this interleave");
+                        if (NEXT && slot % rd_every == 0 && slot <= rd_last) {
                             fr[nxt][slot / rd_every] = read_fragment(slot / rd_every);
                             __builtin_amdgcn_sched_barrier(0);
                         }
-                        if (LOAD && slot >= ld_first && (slot - ld_first) % ld_every == 0 &&
-                            (slot - ld_first) / ld_every < S::loads_per_wave) {
+                        if (NEXT && slot == rd_last + 1) {
+                            advance_read_cursor();
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        if (LOAD && slot >= ld_first && (slot - ld_first) % ld_every == 0 && slot <= ld_last) {
                             issue_load((slot - ld_first) / ld_every);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        if (LOAD && slot == ld_last + 1) {
+                            advance_load_cursor();
                             __builtin_amdgcn_sched_barrier(0);
                         }
                         ++slot;
                     }
-        if (NEXT) advance_read_cursor();
-        if (LOAD) advance_load_cursor();
     };
     using T = std::true_type;
     using F = std::false_type;
