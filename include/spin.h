@@ -133,6 +133,24 @@ spin_status spin_lincomb_trunc(int n, size_t count, int terms, const uint64_t *c
                                const uint64_t *r, const uint64_t *r_top, const uint64_t *r_msb,
                                uint64_t *out, spin_stream stream);
 
+/* Binary sharing (Section 4.1): 64 independent bit positions per word,
+ * x = XOR_i x_i.  XOR of sharings is local (Section 4.3 Addition); AND consumes
+ * a bit triple (a, b, c = a AND b) and is the GF(2) form of the Beaver update.
+ *   spin_bshare:     shares[i][k] = rand64(seed, stream_id, i, k) for i >= 1,
+ *                    shares[0][k] = x[k] XOR (XOR of the others).
+ *   spin_bopen:      out[k] = XOR_i (shares[i][k] XOR mask[i][k]); mask may be NULL.
+ *   spin_beaver_and: e = XOR_i (x_i ^ a_i), f = XOR_i (y_i ^ b_i),
+ *                    z_i = c_i ^ (e & b_i) ^ (a_i & f)  (^ (e & f) for i = 0).
+ * Layouts as for the arithmetic calls: [n][count] words; z may alias an input. */
+spin_status spin_bshare(const uint64_t *x, size_t count, int n, uint64_t seed, uint64_t stream_id,
+                        uint64_t *shares, spin_stream stream);
+spin_status spin_bopen(const uint64_t *shares, const uint64_t *mask, size_t count, int n,
+                       uint64_t *out, spin_stream stream);
+spin_status spin_beaver_and(int n, size_t count,
+                            const uint64_t *x, const uint64_t *y,
+                            const uint64_t *a, const uint64_t *b, const uint64_t *c,
+                            uint64_t *z, spin_stream stream);
+
 /* Per-kernel timing for benchmarks (measurement aid, not part of the protocol).
  * While enabled, every kernel the library launches is bracketed by a pair of
  * HIP events recorded on the caller's stream; events are created on demand
@@ -150,7 +168,8 @@ typedef enum {
     SPIN_KERNEL_GEMM_LIMB = 6,
     SPIN_KERNEL_GEMM_VALU = 7,
     SPIN_KERNEL_LINCOMB = 8,
-    SPIN_KERNEL_COUNT = 9
+    SPIN_KERNEL_BINARY = 9,     /* bshare, bopen, beaver_and */
+    SPIN_KERNEL_COUNT = 10
 } spin_kernel;
 void spin_profile_enable(int on);
 spin_status spin_profile_read(spin_kernel kernel, double *total_ms, unsigned *launches);

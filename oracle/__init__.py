@@ -56,6 +56,12 @@ def lib():
         L.oracle_trunc.argtypes = [i32, sz, i32, i32] + [p] * 5
         L.oracle_local_shift_trunc.argtypes = [i32, sz, i32, p, p]
         L.oracle_threads.restype = i32
+        L.oracle_bshare.argtypes = [p, sz, i32, u64, u64, p]
+        L.oracle_bopen.argtypes = [p, p, sz, i32, p]
+        L.oracle_dealer_and.argtypes = [i32, sz, u64, u64, u64, u64, p, p, p, p]
+        L.oracle_beaver_and.argtypes = [i32, sz] + [p] * 6
+        for name in ("oracle_bshare", "oracle_bopen", "oracle_dealer_and", "oracle_beaver_and"):
+            getattr(L, name).restype = None
         L.oracle_lincomb.argtypes = [i32, sz, i32, i32, p, p, u64, p]
         L.oracle_lincomb.restype = None
         L.oracle_random.argtypes = [p, sz, u64, u64, u64, u64]
@@ -286,3 +292,36 @@ def evaluate_completed_square(x_sh, k4p_log2, t3, t2, t1, t0, p, seed, l=64):
     total = lincomb([v2, flat], [1, _enc1(k4p * t1, p) << shift], _enc1(k4p * t0, 2 * p) << shift, l)
     r, rt, rm = trunc_dealer(n, count, p + shift, seed + 23, l)
     return trunc(total, r, rt, rm, p + shift, l).reshape(x_sh.shape)
+
+
+# ---- binary sharing (Section 4.1), 64 bit positions per word
+def bshare(x, n, seed, stream):
+    x = _u64(x)
+    out = np.empty((n,) + x.shape, dtype=np.uint64)
+    lib().oracle_bshare(_ptr(x), x.size, n, seed, stream, _ptr(out))
+    return out
+
+
+def bopen(shares, mask=None):
+    shares = _u64(shares)
+    out = np.empty(shares.shape[1:], dtype=np.uint64)
+    if mask is not None:
+        mask = _u64(mask)
+    lib().oracle_bopen(_ptr(shares), _ptr(mask), out.size, shares.shape[0], _ptr(out))
+    return out
+
+
+def dealer_and(n, count, seed):
+    a = np.empty((n, count), dtype=np.uint64)
+    b = np.empty((n, count), dtype=np.uint64)
+    c = np.empty((n, count), dtype=np.uint64)
+    s = np.empty((count,), dtype=np.uint64)
+    lib().oracle_dealer_and(n, count, seed, STREAM_A, STREAM_B, STREAM_C, _ptr(a), _ptr(b), _ptr(c), _ptr(s))
+    return a, b, c
+
+
+def beaver_and(x, y, a, b, c):
+    x, y, a, b, c = map(_u64, (x, y, a, b, c))
+    z = np.empty(x.shape, dtype=np.uint64)
+    lib().oracle_beaver_and(x.shape[0], x[0].size, _ptr(x), _ptr(y), _ptr(a), _ptr(b), _ptr(c), _ptr(z))
+    return z

@@ -370,3 +370,70 @@ void oracle_lincomb(int n, size_t count, int l, int terms, const u64 *const *in,
             out[(size_t)i * count + k] = acc & mask;
         }
 }
+
+/* ------------------------------------------------------------------------ */
+/* Binary sharing (Section 4.1): a bit x is split into n bits with x = XOR_i x_i.
+ * Words carry 64 independent bit positions.  Parties 1..n-1 take generator
+ * output, party 0 the residual. */
+void oracle_bshare(const u64 *x, size_t count, int n, u64 seed, u64 stream, u64 *shares)
+{
+    for (size_t k = 0; k < count; ++k) {
+        u64 rest = x[k];
+        for (int i = 1; i < n; ++i) {
+            u64 s = oracle_rand64(seed, stream, (u64)i, k);
+            shares[(size_t)i * count + k] = s;
+            rest ^= s;
+        }
+        shares[k] = rest;
+    }
+}
+
+/* Opening of a binary sharing: out = XOR_i (shares_i XOR mask_i); mask may be NULL. */
+void oracle_bopen(const u64 *shares, const u64 *mask_sh, size_t count, int n, u64 *out)
+{
+    for (size_t k = 0; k < count; ++k) {
+        u64 acc = 0;
+        for (int i = 0; i < n; ++i) {
+            acc ^= shares[(size_t)i * count + k];
+            if (mask_sh) acc ^= mask_sh[(size_t)i * count + k];
+        }
+        out[k] = acc;
+    }
+}
+
+/* Bit triples for AND: a_i, b_i generator output, c = (XOR a_i) AND (XOR b_i), shared. */
+void oracle_dealer_and(int n, size_t count, u64 seed, u64 sA, u64 sB, u64 sC, u64 *a, u64 *b, u64 *c, u64 *scratch)
+{
+    for (int i = 0; i < n; ++i)
+        for (size_t k = 0; k < count; ++k) {
+            a[i * count + k] = oracle_rand64(seed, sA, (u64)i, k);
+            b[i * count + k] = oracle_rand64(seed, sB, (u64)i, k);
+        }
+    for (size_t k = 0; k < count; ++k) {
+        u64 av = 0, bv = 0;
+        for (int i = 0; i < n; ++i) { av ^= a[i * count + k]; bv ^= b[i * count + k]; }
+        scratch[k] = av & bv;
+    }
+    oracle_bshare(scratch, count, n, seed, sC, c);
+}
+
+/* AND of two binary sharings with a bit triple: the GF(2) form of the Beaver
+ * update (XOR for addition, Section 4.3 Addition; AND for multiplication):
+ *   e = XOR_i (x_i ^ a_i), f = XOR_i (y_i ^ b_i) opened,
+ *   z_i = c_i ^ (e & b_i) ^ (a_i & f), and party 0 also XORs in e & f. */
+void oracle_beaver_and(int n, size_t count, const u64 *x, const u64 *y, const u64 *a, const u64 *b,
+                       const u64 *c, u64 *z)
+{
+    for (size_t k = 0; k < count; ++k) {
+        u64 e = 0, f = 0;
+        for (int i = 0; i < n; ++i) {
+            e ^= x[i * count + k] ^ a[i * count + k];
+            f ^= y[i * count + k] ^ b[i * count + k];
+        }
+        for (int i = 0; i < n; ++i) {
+            u64 v = c[i * count + k] ^ (e & b[i * count + k]) ^ (a[i * count + k] & f);
+            if (i == 0) v ^= e & f;
+            z[i * count + k] = v;
+        }
+    }
+}

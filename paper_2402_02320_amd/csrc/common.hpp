@@ -69,6 +69,10 @@ spin_status launch_beaver_mul(int n, size_t count, const u64 *x, const u64 *y, c
 spin_status launch_trunc(int n, size_t count, int f, const u64 *x, const u64 *r, const u64 *r_top,
                          const u64 *r_msb, u64 *out, hipStream_t s);
 
+spin_status launch_bshare(const u64 *x, size_t count, int n, const PartyKeys &keys, u64 *shares, hipStream_t s);
+spin_status launch_bopen(const u64 *shares, const u64 *mask, size_t count, int n, u64 *out, hipStream_t s);
+spin_status launch_beaver_and(int n, size_t count, const u64 *x, const u64 *y, const u64 *a, const u64 *b,
+                              const u64 *c, u64 *z, hipStream_t s);
 struct LincombTerms { const u64 *in[SPIN_MAX_TERMS]; u64 coef[SPIN_MAX_TERMS]; int terms; };
 spin_status launch_lincomb_trunc(int n, size_t count, const LincombTerms &t, u64 constant, int f, const u64 *r,
                                  const u64 *r_top, const u64 *r_msb, u64 *out, hipStream_t s);

@@ -167,6 +167,64 @@ __global__ __launch_bounds__(kBlock) void lincomb_trunc_kernel(LincombTerms t, u
     }
 }
 
+// ---- binary sharing: the same three streams with XOR for + and AND for * (Section 4.1, 4.3) ----
+template <int NP>
+__global__ __launch_bounds__(kBlock) void bshare_kernel(const u64 *__restrict__ x, size_t count, PartyKeys keys,
+                                                       u64 *__restrict__ shares)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= count) return;
+    u64 rest = x[v];
+#pragma unroll
+    for (int i = 1; i < NP; ++i) {
+        u64 s = absorb(keys.key[i], v);
+        shares[(size_t)i * count + v] = s;
+        rest ^= s;
+    }
+    shares[v] = rest;
+}
+
+template <int NP, bool MASK>
+__global__ __launch_bounds__(kBlock) void bopen_kernel(const u64 *__restrict__ shares, const u64 *__restrict__ mask,
+                                                      size_t count, u64 *__restrict__ out)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= count) return;
+    u64 s[NP], m[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        s[i] = shares[(size_t)i * count + v];
+        if (MASK) m[i] = mask[(size_t)i * count + v];
+    }
+    u64 acc = 0;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) acc ^= MASK ? s[i] ^ m[i] : s[i];
+    out[v] = acc;
+}
+
+template <int NP>
+__global__ __launch_bounds__(kBlock) void beaver_and_kernel(const u64 *x, const u64 *y, const u64 *a, const u64 *b,
+                                                           const u64 *c, size_t count, u64 *z)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= count) return;
+    u64 xv[NP], yv[NP], av[NP], bv[NP], cv[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        size_t o = (size_t)i * count + v;
+        xv[i] = x[o]; yv[i] = y[o]; av[i] = a[o]; bv[i] = b[o]; cv[i] = c[o];
+    }
+    u64 e = 0, f = 0;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) { e ^= xv[i] ^ av[i]; f ^= yv[i] ^ bv[i]; }
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        u64 bi = bv[i];
+        if (i == 0) bi ^= f;                       // (e & b_0) ^ (e & f) = e & (b_0 ^ f)
+        z[(size_t)i * count + v] = cv[i] ^ (e & bi) ^ (av[i] & f);
+    }
+}
+
 inline unsigned grid_for(size_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
 
 }  // namespace
@@ -224,6 +282,36 @@ spin_status launch_trunc(int n, size_t count, int f, const u64 *x, const u64 *r,
         trunc_kernel<decltype(np)::value><<<grid_for(count), kBlock, 0, s>>>(x, r, r_top, r_msb, count, f, out);
     });
     return check_launch("spin_trunc");
+}
+
+spin_status launch_bshare(const u64 *x, size_t count, int n, const PartyKeys &keys, u64 *shares, hipStream_t s)
+{
+    KernelTimer timer(SPIN_KERNEL_BINARY, s);
+    for_party_count(n, [&](auto np) {
+        bshare_kernel<decltype(np)::value><<<grid_for(count), kBlock, 0, s>>>(x, count, keys, shares);
+    });
+    return check_launch("spin_bshare");
+}
+
+spin_status launch_bopen(const u64 *shares, const u64 *mask, size_t count, int n, u64 *out, hipStream_t s)
+{
+    KernelTimer timer(SPIN_KERNEL_BINARY, s);
+    for_party_count(n, [&](auto np) {
+        constexpr int NP = decltype(np)::value;
+        if (mask) bopen_kernel<NP, true><<<grid_for(count), kBlock, 0, s>>>(shares, mask, count, out);
+        else bopen_kernel<NP, false><<<grid_for(count), kBlock, 0, s>>>(shares, nullptr, count, out);
+    });
+    return check_launch("spin_bopen");
+}
+
+spin_status launch_beaver_and(int n, size_t count, const u64 *x, const u64 *y, const u64 *a, const u64 *b,
+                              const u64 *c, u64 *z, hipStream_t s)
+{
+    KernelTimer timer(SPIN_KERNEL_BINARY, s);
+    for_party_count(n, [&](auto np) {
+        beaver_and_kernel<decltype(np)::value><<<grid_for(count), kBlock, 0, s>>>(x, y, a, b, c, count, z);
+    });
+    return check_launch("spin_beaver_and");
 }
 
 spin_status launch_lincomb_trunc(int n, size_t count, const LincombTerms &t, u64 constant, int f, const u64 *r,

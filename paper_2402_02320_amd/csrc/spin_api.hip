@@ -169,6 +169,34 @@ spin_status spin_profile_read(spin_kernel kernel, double *total_ms, unsigned *la
     return SPIN_OK;
 }
 
+spin_status spin_bshare(const uint64_t *x, size_t count, int n, uint64_t seed, uint64_t stream_id,
+                        uint64_t *shares, spin_stream stream)
+{
+    if (bad_ptr(x) || bad_ptr(shares) || bad_n(n) || count == 0) return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    PartyKeys keys;
+    for (int i = 0; i < SPIN_MAX_PARTIES; ++i) keys.key[i] = stream_key(seed, stream_id, (u64)i);
+    return launch_bshare(x, count, n, keys, shares, (hipStream_t)stream);
+}
+
+spin_status spin_bopen(const uint64_t *shares, const uint64_t *mask, size_t count, int n, uint64_t *out,
+                       spin_stream stream)
+{
+    if (bad_ptr(shares) || bad_ptr(out) || (mask && !aligned16(mask)) || bad_n(n) || count == 0)
+        return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    return launch_bopen(shares, mask, count, n, out, (hipStream_t)stream);
+}
+
+spin_status spin_beaver_and(int n, size_t count, const uint64_t *x, const uint64_t *y, const uint64_t *a,
+                            const uint64_t *b, const uint64_t *c, uint64_t *z, spin_stream stream)
+{
+    if (bad_ptr(x) || bad_ptr(y) || bad_ptr(a) || bad_ptr(b) || bad_ptr(c) || bad_ptr(z) || bad_n(n) || count == 0)
+        return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    return launch_beaver_and(n, count, x, y, a, b, c, z, (hipStream_t)stream);
+}
+
 spin_status spin_lincomb_trunc(int n, size_t count, int terms, const uint64_t *const *in, const uint64_t *coef,
                                uint64_t constant, int f, const uint64_t *r, const uint64_t *r_top,
                                const uint64_t *r_msb, uint64_t *out, spin_stream stream)

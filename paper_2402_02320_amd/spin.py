@@ -41,6 +41,11 @@ def lib():
         L.spin_trunc.argtypes = [i32, sz, i32] + [p] * 5 + [p]
         L.spin_lincomb_trunc.argtypes = [i32, sz, i32, p, p, u64, i32, p, p, p, p, p]
         L.spin_lincomb_trunc.restype = i32
+        L.spin_bshare.argtypes = [p, sz, i32, u64, u64, p, p]
+        L.spin_bopen.argtypes = [p, p, sz, i32, p, p]
+        L.spin_beaver_and.argtypes = [i32, sz] + [p] * 6 + [p]
+        for name in ("spin_bshare", "spin_bopen", "spin_beaver_and"):
+            getattr(L, name).restype = i32
         for name in ("spin_random", "spin_share", "spin_open", "spin_beaver_matmul", "spin_beaver_mul", "spin_trunc"):
             getattr(L, name).restype = i32
         L.spin_profile_enable.argtypes = [i32]
@@ -148,6 +153,36 @@ def trunc(x, r, r_top, r_msb, f, out=None):
     return out
 
 
+def bshare(x, n, seed, stream_id, out=None):
+    if out is None:
+        out = torch.empty((n,) + tuple(x.shape), dtype=torch.int64, device=x.device)
+    _check(lib().spin_bshare(_dev(x, "x"), x.numel(), n, seed, stream_id, _dev(out, "shares"), _stream()))
+    return out
+
+
+def bopen(shares, mask=None, out=None):
+    n = shares.shape[0]
+    if out is None:
+        out = torch.empty(tuple(shares.shape[1:]), dtype=torch.int64, device=shares.device)
+    if mask is not None and mask.shape != shares.shape:
+        raise SpinError("mask must have the shape of shares")
+    _check(lib().spin_bopen(_dev(shares, "shares"), None if mask is None else _dev(mask, "mask"),
+                            out.numel(), n, _dev(out, "out"), _stream()))
+    return out
+
+
+def beaver_and(x, y, a, b, c, out=None):
+    n = x.shape[0]
+    for t in (y, a, b, c):
+        if t.shape != x.shape:
+            raise SpinError("inconsistent operand shapes")
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib().spin_beaver_and(n, x[0].numel(), _dev(x, "x"), _dev(y, "y"), _dev(a, "a"), _dev(b, "b"),
+                                 _dev(c, "c"), _dev(out, "z"), _stream()))
+    return out
+
+
 def lincomb_trunc(terms, coefs, constant=0, f=0, tuple_=None, out=None):
     """out = Truncate(sum_j coefs[j] * terms[j] + constant, f); f = 0 leaves the sum untruncated."""
     n = terms[0].shape[0]
@@ -170,7 +205,7 @@ def lincomb_trunc(terms, coefs, constant=0, f=0, tuple_=None, out=None):
 
 
 KERNELS = {"random": 0, "share": 1, "open": 2, "beaver_mul": 3, "trunc": 4, "pack": 5, "gemm_limb": 6,
-           "gemm_valu": 7, "lincomb": 8}
+           "gemm_valu": 7, "lincomb": 8, "binary": 9}
 
 
 def profile_enable(on=True):
