@@ -13,6 +13,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "spin_oracle.c")
+_SRC128 = os.path.join(_HERE, "spin_oracle128.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 # stream ids of the synthetic generator (which tensor a random word belongs to)
@@ -22,11 +23,11 @@ STREAM_R, STREAM_RTOP, STREAM_RMSB = 6, 7, 8
 
 def build(force=True):
     """Compile the oracle with gcc (-O2, OpenMP for the row loops)."""
-    stale = not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SRC128))
     if force or stale:
         subprocess.check_call(
             ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
-             "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
+             "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC128, "-lm"])
     return _LIB
 
 
@@ -56,6 +57,18 @@ def lib():
         L.oracle_trunc.argtypes = [i32, sz, i32, i32] + [p] * 5
         L.oracle_local_shift_trunc.argtypes = [i32, sz, i32, p, p]
         L.oracle_threads.restype = i32
+        L.oracle128_share.argtypes = [p, sz, i32, u64, u64, p]
+        L.oracle128_open.argtypes = [p, p, sz, i32, p]
+        L.oracle128_ring_matmul.argtypes = [p, p, i32, i32, i32, p]
+        L.oracle128_dealer_matmul.argtypes = [i32, i32, i32, i32, i32, u64, u64, u64, u64] + [p] * 6
+        L.oracle128_dealer_mul.argtypes = [i32, sz, u64, u64, u64, u64, p, p, p, p]
+        L.oracle128_beaver_matmul.argtypes = [i32] * 5 + [p] * 8
+        L.oracle128_beaver_mul.argtypes = [i32, sz] + [p] * 6
+        L.oracle128_trunc_dealer.argtypes = [i32, sz, i32, u64, u64, u64, u64, p, p, p, p]
+        L.oracle128_trunc.argtypes = [i32, sz, i32] + [p] * 5
+        for name in ("share", "open", "ring_matmul", "dealer_matmul", "dealer_mul", "beaver_matmul", "beaver_mul",
+                     "trunc_dealer", "trunc"):
+            getattr(L, "oracle128_" + name).restype = None
         L.oracle_bshare.argtypes = [p, sz, i32, u64, u64, p]
         L.oracle_bopen.argtypes = [p, p, sz, i32, p]
         L.oracle_dealer_and.argtypes = [i32, sz, u64, u64, u64, u64, p, p, p, p]
@@ -325,3 +338,103 @@ def beaver_and(x, y, a, b, c):
     z = np.empty(x.shape, dtype=np.uint64)
     lib().oracle_beaver_and(x.shape[0], x[0].size, _ptr(x), _ptr(y), _ptr(a), _ptr(b), _ptr(c), _ptr(z))
     return z
+
+
+# ---- ring Z_2^128: arrays carry a trailing axis of two uint64 words (low, high) ----------------------
+class r128:
+    """Wrappers of oracle/spin_oracle128.c.  A ring tensor of shape S is a uint64 array of shape S + (2,)."""
+
+    @staticmethod
+    def _w(a):
+        a = _u64(a)
+        assert a.shape[-1] == 2
+        return a
+
+    @staticmethod
+    def from_ints(values, shape=None):
+        flat = [int(v) % (1 << 128) for v in np.asarray(values, dtype=object).ravel()]
+        out = np.array([[v & ((1 << 64) - 1), v >> 64] for v in flat], dtype=np.uint64)
+        shp = np.asarray(values, dtype=object).shape if shape is None else shape
+        return out.reshape(tuple(shp) + (2,))
+
+    @staticmethod
+    def to_ints(a):
+        a = r128._w(a)
+        lo, hi = a[..., 0].astype(object), a[..., 1].astype(object)
+        return lo + hi * (1 << 64)
+
+    @staticmethod
+    def share(x, n, seed, stream):
+        x = r128._w(x)
+        out = np.empty((n,) + x.shape, dtype=np.uint64)
+        lib().oracle128_share(_ptr(x), x.size // 2, n, seed, stream, _ptr(out))
+        return out
+
+    @staticmethod
+    def open_(shares, mask=None):
+        shares = r128._w(shares)
+        out = np.empty(shares.shape[1:], dtype=np.uint64)
+        if mask is not None:
+            mask = r128._w(mask)
+        lib().oracle128_open(_ptr(shares), _ptr(mask), out.size // 2, shares.shape[0], _ptr(out))
+        return out
+
+    @staticmethod
+    def ring_matmul(P, Q):
+        P, Q = r128._w(P), r128._w(Q)
+        M, K, _ = P.shape
+        N = Q.shape[1]
+        out = np.empty((M, N, 2), dtype=np.uint64)
+        lib().oracle128_ring_matmul(_ptr(P), _ptr(Q), M, N, K, _ptr(out))
+        return out
+
+    @staticmethod
+    def dealer_matmul(n, batch, M, N, K, seed):
+        A = np.empty((n, batch, M, K, 2), dtype=np.uint64)
+        B = np.empty((n, batch, K, N, 2), dtype=np.uint64)
+        C = np.empty((n, batch, M, N, 2), dtype=np.uint64)
+        sa, sb, sc = (np.empty(t.shape[1:], dtype=np.uint64) for t in (A, B, C))
+        lib().oracle128_dealer_matmul(n, batch, M, N, K, seed, STREAM_A, STREAM_B, STREAM_C,
+                                      _ptr(A), _ptr(B), _ptr(C), _ptr(sa), _ptr(sb), _ptr(sc))
+        return A, B, C
+
+    @staticmethod
+    def dealer_mul(n, count, seed):
+        a, b, c = (np.empty((n, count, 2), dtype=np.uint64) for _ in range(3))
+        s = np.empty((count, 2), dtype=np.uint64)
+        lib().oracle128_dealer_mul(n, count, seed, STREAM_A, STREAM_B, STREAM_C, _ptr(a), _ptr(b), _ptr(c), _ptr(s))
+        return a, b, c
+
+    @staticmethod
+    def beaver_matmul(X, Y, A, B, C):
+        X, Y, A, B, C = map(r128._w, (X, Y, A, B, C))
+        n, batch, M, K, _ = X.shape
+        N = Y.shape[3]
+        Z = np.empty((n, batch, M, N, 2), dtype=np.uint64)
+        E = np.empty((batch, M, K, 2), dtype=np.uint64)
+        F = np.empty((batch, K, N, 2), dtype=np.uint64)
+        lib().oracle128_beaver_matmul(n, batch, M, N, K, _ptr(X), _ptr(Y), _ptr(A), _ptr(B), _ptr(C), _ptr(Z),
+                                      _ptr(E), _ptr(F))
+        return Z
+
+    @staticmethod
+    def beaver_mul(x, y, a, b, c):
+        x, y, a, b, c = map(r128._w, (x, y, a, b, c))
+        z = np.empty(x.shape, dtype=np.uint64)
+        lib().oracle128_beaver_mul(x.shape[0], x[0].size // 2, _ptr(x), _ptr(y), _ptr(a), _ptr(b), _ptr(c), _ptr(z))
+        return z
+
+    @staticmethod
+    def trunc_dealer(n, count, f, seed):
+        r, rt, rm = (np.empty((n, count, 2), dtype=np.uint64) for _ in range(3))
+        s = np.empty((count, 2), dtype=np.uint64)
+        lib().oracle128_trunc_dealer(n, count, f, seed, STREAM_R, STREAM_RTOP, STREAM_RMSB,
+                                     _ptr(r), _ptr(rt), _ptr(rm), _ptr(s))
+        return r, rt, rm
+
+    @staticmethod
+    def trunc(x, r, r_top, r_msb, f):
+        x, r, r_top, r_msb = map(r128._w, (x, r, r_top, r_msb))
+        out = np.empty(x.shape, dtype=np.uint64)
+        lib().oracle128_trunc(x.shape[0], x[0].size // 2, f, _ptr(x), _ptr(r), _ptr(r_top), _ptr(r_msb), _ptr(out))
+        return out
