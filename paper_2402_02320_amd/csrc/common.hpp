@@ -14,6 +14,7 @@ namespace spin {
 
 typedef uint64_t u64;
 typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+typedef unsigned __int128 u128;   // ring Z_2^128: 16 bytes, little-endian (low word first)
 
 // ---- counter generator (specified in include/spin.h at spin_random) --------
 __host__ __device__ inline u64 mix64(u64 z)
@@ -63,11 +64,15 @@ struct KernelTimer {
 // ---- internal launchers (defined in the .hip files) -------------------------
 spin_status launch_random(u64 *out, size_t count, u64 key, u64 first_idx, hipStream_t s);
 spin_status launch_share(const u64 *x, size_t count, int n, const PartyKeys &keys, u64 *shares, hipStream_t s);
-spin_status launch_open(const u64 *shares, const u64 *mask, size_t count, int n, u64 *out, hipStream_t s);
-spin_status launch_beaver_mul(int n, size_t count, const u64 *x, const u64 *y, const u64 *a, const u64 *b,
-                              const u64 *c, u64 *z, hipStream_t s);
-spin_status launch_trunc(int n, size_t count, int f, const u64 *x, const u64 *r, const u64 *r_top,
-                         const u64 *r_msb, u64 *out, hipStream_t s);
+// T = u64 or u128 (instantiated in elementwise.hip)
+template <class T> spin_status launch_open(const T *shares, const T *mask, size_t count, int n, T *out, hipStream_t s);
+template <class T>
+spin_status launch_beaver_mul(int n, size_t count, const T *x, const T *y, const T *a, const T *b, const T *c, T *z,
+                              hipStream_t s);
+template <class T>
+spin_status launch_trunc(int n, size_t count, int f, const T *x, const T *r, const T *r_top, const T *r_msb, T *out,
+                         hipStream_t s);
+spin_status launch_share128(const u128 *x, size_t count, int n, const PartyKeys &keys, u128 *shares, hipStream_t s);
 
 spin_status launch_bshare(const u64 *x, size_t count, int n, const PartyKeys &keys, u64 *shares, hipStream_t s);
 spin_status launch_bopen(const u64 *shares, const u64 *mask, size_t count, int n, u64 *out, hipStream_t s);
@@ -77,14 +82,17 @@ struct LincombTerms { const u64 *in[SPIN_MAX_TERMS]; u64 coef[SPIN_MAX_TERMS]; i
 spin_status launch_lincomb_trunc(int n, size_t count, const LincombTerms &t, u64 constant, int f, const u64 *r,
                                  const u64 *r_top, const u64 *r_msb, u64 *out, hipStream_t s);
 
-struct MatmulArgs {
+template <class T> struct MatmulArgsT {
     int n, batch, M, N, K;
-    const u64 *X, *Y, *A, *B, *C;
-    u64 *Z;
+    const T *X, *Y, *A, *B, *C;
+    T *Z;
     void *workspace;
 };
-size_t valu_workspace_bytes(int n, int batch, int M, int N, int K);
-spin_status launch_matmul_valu(const MatmulArgs &a, hipStream_t s);
+typedef MatmulArgsT<u64> MatmulArgs;
+typedef MatmulArgsT<u128> MatmulArgs128;
+// elem_bytes = 8 (Z_2^64) or 16 (Z_2^128)
+size_t valu_workspace_bytes(int n, int batch, int M, int N, int K, int elem_bytes);
+template <class T> spin_status launch_matmul_valu(const MatmulArgsT<T> &a, hipStream_t s);
 size_t limb_workspace_bytes(int n, int batch, int M, int N, int K);
 spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s);
 

@@ -22,12 +22,19 @@ constexpr int kBlock = 256;
 template <class V> struct Lanes;
 template <> struct Lanes<u64x2> { static constexpr int width = 2; };
 template <> struct Lanes<u64>   { static constexpr int width = 1; };
+template <> struct Lanes<u128>  { static constexpr int width = 1; };
 
 template <class V> __device__ inline V gen(u64 key, u64 idx);
 template <> __device__ inline u64 gen<u64>(u64 key, u64 idx) { return absorb(key, idx); }
 template <> __device__ inline u64x2 gen<u64x2>(u64 key, u64 idx)
 {
     u64x2 v; v.x = absorb(key, idx); v.y = absorb(key, idx + 1); return v;
+}
+
+// a 128-bit generator word is the pair of 64-bit outputs 2 idx (low) and 2 idx + 1 (high)
+template <> __device__ inline u128 gen<u128>(u64 key, u64 idx)
+{
+    return (u128)absorb(key, 2 * idx) | ((u128)absorb(key, 2 * idx + 1) << 64);
 }
 
 template <class V>
@@ -56,19 +63,19 @@ __global__ __launch_bounds__(kBlock) void share_kernel(const V *__restrict__ x, 
 }
 
 // out = sum_i (shares_i - mask_i): the party-axis reduction that replaces the network exchange.
-template <int NP, bool MASK>
-__global__ __launch_bounds__(kBlock) void open_kernel(const u64 *__restrict__ shares, const u64 *__restrict__ mask,
-                                                     size_t count, u64 *__restrict__ out)
+template <int NP, bool MASK, class T>
+__global__ __launch_bounds__(kBlock) void open_kernel(const T *__restrict__ shares, const T *__restrict__ mask,
+                                                     size_t count, T *__restrict__ out)
 {
     size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (v >= count) return;
-    u64 s[NP], m[NP];
+    T s[NP], m[NP];
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
         s[i] = shares[(size_t)i * count + v];
         if (MASK) m[i] = mask[(size_t)i * count + v];
     }
-    u64 acc = 0;
+    T acc = 0;
 #pragma unroll
     for (int i = 0; i < NP; ++i) acc += MASK ? s[i] - m[i] : s[i];
     out[v] = acc;
@@ -76,24 +83,24 @@ __global__ __launch_bounds__(kBlock) void open_kernel(const u64 *__restrict__ sh
 
 // z_i = c_i + e*b_i + a_i*f (+ e*f for party 0) with e, f opened in registers (Section 4.3).
 // z may alias an input: a thread reads all of its inputs before it writes.
-template <int NP>
-__global__ __launch_bounds__(kBlock) void beaver_mul_kernel(const u64 *x, const u64 *y, const u64 *a, const u64 *b,
-                                                           const u64 *c, size_t count, u64 *z)
+template <int NP, class T>
+__global__ __launch_bounds__(kBlock) void beaver_mul_kernel(const T *x, const T *y, const T *a, const T *b,
+                                                           const T *c, size_t count, T *z)
 {
     size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (v >= count) return;
-    u64 xv[NP], yv[NP], av[NP], bv[NP], cv[NP];
+    T xv[NP], yv[NP], av[NP], bv[NP], cv[NP];
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
         size_t o = (size_t)i * count + v;
         xv[i] = x[o]; yv[i] = y[o]; av[i] = a[o]; bv[i] = b[o]; cv[i] = c[o];
     }
-    u64 e = 0, f = 0;
+    T e = 0, f = 0;
 #pragma unroll
     for (int i = 0; i < NP; ++i) { e += xv[i] - av[i]; f += yv[i] - bv[i]; }
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
-        u64 bi = bv[i];
+        T bi = bv[i];
         if (i == 0) bi += f;                       // folds the public e*f into party 0's term
         z[(size_t)i * count + v] = cv[i] + e * bi + av[i] * f;
     }
@@ -101,42 +108,42 @@ __global__ __launch_bounds__(kBlock) void beaver_mul_kernel(const u64 *x, const 
 
 // The combine of the signed probabilistic truncation (Section 4.4) on party shares y[] held in
 // registers; steps as listed at spin_trunc in include/spin.h.
-template <int NP>
-__device__ inline void truncate_and_store(const u64 (&y)[NP], const u64 *__restrict__ r,
-                                          const u64 *__restrict__ r_top, const u64 *__restrict__ r_msb, size_t count,
-                                          size_t v, int f, u64 *out)
+template <int NP, class T>
+__device__ inline void truncate_and_store(const T (&y)[NP], const T *__restrict__ r, const T *__restrict__ r_top,
+                                          const T *__restrict__ r_msb, size_t count, size_t v, int f, T *out)
 {
-    u64 rt[NP], rm[NP];
-    u64 c = (u64)1 << 62;
+    constexpr int L = 8 * sizeof(T);               // ring width l
+    T rt[NP], rm[NP];
+    T c = (T)1 << (L - 2);
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
         size_t o = (size_t)i * count + v;
         rt[i] = r_top[o]; rm[i] = r_msb[o];
         c += y[i] + r[o];
     }
-    const u64 topmask = (((u64)1 << (63 - f)) - 1);
-    const u64 c_msb = c >> 63;
-    const u64 c_top = (c >> f) & topmask;
+    const T topmask = (((T)1 << (L - 1 - f)) - 1);
+    const T c_msb = c >> (L - 1);
+    const T c_top = (c >> f) & topmask;
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
-        u64 b = rm[i] - 2 * c_msb * rm[i];
-        u64 o = (b << (63 - f)) - rt[i];
-        if (i == 0) o += (c_msb << (63 - f)) + c_top - ((u64)1 << (62 - f));
+        T b = rm[i] - 2 * c_msb * rm[i];
+        T o = (b << (L - 1 - f)) - rt[i];
+        if (i == 0) o += (c_msb << (L - 1 - f)) + c_top - ((T)1 << (L - 2 - f));
         out[(size_t)i * count + v] = o;
     }
 }
 
-template <int NP>
-__global__ __launch_bounds__(kBlock) void trunc_kernel(const u64 *x, const u64 *__restrict__ r,
-                                                      const u64 *__restrict__ r_top, const u64 *__restrict__ r_msb,
-                                                      size_t count, int f, u64 *out)
+template <int NP, class T>
+__global__ __launch_bounds__(kBlock) void trunc_kernel(const T *x, const T *__restrict__ r,
+                                                      const T *__restrict__ r_top, const T *__restrict__ r_msb,
+                                                      size_t count, int f, T *out)
 {
     size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (v >= count) return;
-    u64 y[NP];
+    T y[NP];
 #pragma unroll
     for (int i = 0; i < NP; ++i) y[i] = x[(size_t)i * count + v];
-    truncate_and_store<NP>(y, r, r_top, r_msb, count, v, f, out);
+    truncate_and_store<NP, T>(y, r, r_top, r_msb, count, v, f, out);
 }
 
 // y_i = sum_j coef_j in_j,i (+ constant for party 0), then the truncation above when TRUNC
@@ -160,7 +167,7 @@ __global__ __launch_bounds__(kBlock) void lincomb_trunc_kernel(LincombTerms t, u
         for (int i = 0; i < NP; ++i) y[i] += cf * src[(size_t)i * count + v];
     }
     if (TRUNC) {
-        truncate_and_store<NP>(y, r, r_top, r_msb, count, v, f, out);
+        truncate_and_store<NP, u64>(y, r, r_top, r_msb, count, v, f, out);
     } else {
 #pragma unroll
         for (int i = 0; i < NP; ++i) out[(size_t)i * count + v] = y[i];
@@ -253,36 +260,59 @@ spin_status launch_share(const u64 *x, size_t count, int n, const PartyKeys &key
     return check_launch("spin_share");
 }
 
-spin_status launch_open(const u64 *shares, const u64 *mask, size_t count, int n, u64 *out, hipStream_t s)
+template <class T>
+spin_status launch_open(const T *shares, const T *mask, size_t count, int n, T *out, hipStream_t s)
 {
     KernelTimer timer(SPIN_KERNEL_OPEN, s);
     for_party_count(n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
-        if (mask) open_kernel<NP, true><<<grid_for(count), kBlock, 0, s>>>(shares, mask, count, out);
-        else open_kernel<NP, false><<<grid_for(count), kBlock, 0, s>>>(shares, nullptr, count, out);
+        if (mask) open_kernel<NP, true, T><<<grid_for(count), kBlock, 0, s>>>(shares, mask, count, out);
+        else open_kernel<NP, false, T><<<grid_for(count), kBlock, 0, s>>>(shares, nullptr, count, out);
     });
     return check_launch("spin_open");
 }
 
-spin_status launch_beaver_mul(int n, size_t count, const u64 *x, const u64 *y, const u64 *a, const u64 *b,
-                              const u64 *c, u64 *z, hipStream_t s)
+template <class T>
+spin_status launch_beaver_mul(int n, size_t count, const T *x, const T *y, const T *a, const T *b, const T *c, T *z,
+                              hipStream_t s)
 {
     KernelTimer timer(SPIN_KERNEL_BEAVER_MUL, s);
     for_party_count(n, [&](auto np) {
-        beaver_mul_kernel<decltype(np)::value><<<grid_for(count), kBlock, 0, s>>>(x, y, a, b, c, count, z);
+        beaver_mul_kernel<decltype(np)::value, T><<<grid_for(count), kBlock, 0, s>>>(x, y, a, b, c, count, z);
     });
     return check_launch("spin_beaver_mul");
 }
 
-spin_status launch_trunc(int n, size_t count, int f, const u64 *x, const u64 *r, const u64 *r_top,
-                         const u64 *r_msb, u64 *out, hipStream_t s)
+template <class T>
+spin_status launch_trunc(int n, size_t count, int f, const T *x, const T *r, const T *r_top, const T *r_msb, T *out,
+                         hipStream_t s)
 {
     KernelTimer timer(SPIN_KERNEL_TRUNC, s);
     for_party_count(n, [&](auto np) {
-        trunc_kernel<decltype(np)::value><<<grid_for(count), kBlock, 0, s>>>(x, r, r_top, r_msb, count, f, out);
+        trunc_kernel<decltype(np)::value, T><<<grid_for(count), kBlock, 0, s>>>(x, r, r_top, r_msb, count, f, out);
     });
     return check_launch("spin_trunc");
 }
+
+spin_status launch_share128(const u128 *x, size_t count, int n, const PartyKeys &keys, u128 *shares, hipStream_t s)
+{
+    KernelTimer timer(SPIN_KERNEL_SHARE, s);
+    for_party_count(n, [&](auto np) {
+        share_kernel<decltype(np)::value, u128><<<grid_for(count), kBlock, 0, s>>>(x, count, keys, shares);
+    });
+    return check_launch("spin128_share");
+}
+
+template spin_status launch_open<u64>(const u64 *, const u64 *, size_t, int, u64 *, hipStream_t);
+template spin_status launch_open<u128>(const u128 *, const u128 *, size_t, int, u128 *, hipStream_t);
+template spin_status launch_beaver_mul<u64>(int, size_t, const u64 *, const u64 *, const u64 *, const u64 *, const u64 *,
+                                            u64 *, hipStream_t);
+template spin_status launch_beaver_mul<u128>(int, size_t, const u128 *, const u128 *, const u128 *, const u128 *,
+                                             const u128 *, u128 *, hipStream_t);
+template spin_status launch_trunc<u64>(int, size_t, int, const u64 *, const u64 *, const u64 *, const u64 *, u64 *,
+                                       hipStream_t);
+template spin_status launch_trunc<u128>(int, size_t, int, const u128 *, const u128 *, const u128 *, const u128 *,
+                                        u128 *, hipStream_t);
 
 spin_status launch_bshare(const u64 *x, size_t count, int n, const PartyKeys &keys, u64 *shares, hipStream_t s)
 {

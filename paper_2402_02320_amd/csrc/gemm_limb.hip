@@ -13,15 +13,13 @@
 // complement), which leaves those bits right.  The host splits the inner
 // dimension into chunks of at most kMaxChunkTiles k-tiles per operand pair.
 //
-// Two kernels:
-//  pack_left/right_kernel  open E (or F), convert E/A_i (or F/B_i') to digits and
-//                store them as 1 KiB MFMA fragments: [slot][batch][blk][kt]
-//                [digit][lane*16 + j] = digit of element (blk*32 + lane%32,
-//                kt*32 + 16*(lane/32) + j).  Zero padded to whole tiles.
+// Kernels:
+//  pack_left/right_kernel (limb_common.hpp)  open E (or F), convert E/A_i (or F/B_i') to
+//                digits and store them as 1 KiB MFMA fragments.
 //  limb_gemm_kernel  per party: Z_i = C_i + [E | A_i] . [B_i' ; F], fragments
 //                streamed global -> LDS with direct-to-LDS loads, 36 MFMAs per
 //                32x32x32 step into 8 diagonal accumulators, recombined once.
-#include "common.hpp"
+#include "limb_common.hpp"
 
 // Interleave of one k-step of the GEMM (slots = MFMA index within the step, 72 per step for the 64x32
 // wave tile): an LDS read after every RD_EVERY-th MFMA from slot 0, a direct-to-LDS load after every
@@ -39,192 +37,8 @@
 namespace spin {
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-typedef unsigned int u32;
-
-constexpr int kFrag = 1024;          // bytes of one 32x32 int8 fragment
 constexpr int kDigits = 8;
 constexpr int kMaxChunkTiles = 511;  // 2*511*32 = 32704 < 2^15 digit products per accumulator
-
-// ------------------------------------------------------------------ pack ---
-__device__ inline u64 to_digits(u64 a)
-{
-    return (a + 0x8080808080808080ull) ^ 0x8080808080808080ull;
-}
-
-// Transposes 16 digit-words (16 elements x 8 digits) into 8 rows of 16 bytes
-// and stores row p at dst + p*kFrag.
-__device__ inline void store_digit_rows(const u64 (&w)[16], char *dst)
-{
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {          // digits 0-3 from the low words, 4-7 from the high words
-        u32 rows[4][4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            u32 w0 = (u32)(w[4 * q + 0] >> (32 * half)), w1 = (u32)(w[4 * q + 1] >> (32 * half));
-            u32 w2 = (u32)(w[4 * q + 2] >> (32 * half)), w3 = (u32)(w[4 * q + 3] >> (32 * half));
-            // 4x4 byte transpose with v_perm_b32 (selector 0-3: second operand, 4-7: first operand)
-            u32 t0 = __builtin_amdgcn_perm(w1, w0, 0x05010400u);   // w0.b0 w1.b0 w0.b1 w1.b1
-            u32 t1 = __builtin_amdgcn_perm(w1, w0, 0x07030602u);   // w0.b2 w1.b2 w0.b3 w1.b3
-            u32 t2 = __builtin_amdgcn_perm(w3, w2, 0x05010400u);
-            u32 t3 = __builtin_amdgcn_perm(w3, w2, 0x07030602u);
-            rows[0][q] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
-            rows[1][q] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
-            rows[2][q] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
-            rows[3][q] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
-        }
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            v4i v = {(int)rows[p][0], (int)rows[p][1], (int)rows[p][2], (int)rows[p][3]};
-            *(v4i *)(dst + (size_t)(half * 4 + p) * kFrag) = v;
-        }
-    }
-}
-
-struct PackArgs {
-    const u64 *val;     // X or Y shares   [n][batch][R][Cc]
-    const u64 *tri;     // A or B shares   [n][batch][R][Cc]
-    char *pack;         // [n+1][batch][nblk][KT][8][1024]
-    int n, batch;
-    int rows, cols;     // source matrix is rows x cols, row-major
-    int nblk, KT;       // blocks of 32 along the non-contracted axis; k-tiles of 32
-};
-
-// Both pack kernels make one pass over the 2n share streams of their side: every party's value and
-// triple share is read exactly once; the opened matrix (E or F) accumulates in registers while each
-// triple share is converted and stored as it arrives.  Slots: 0 = opened, 1 + i = party i's triple
-// share (left side A_i; right side B_i, and for party 0 B_0 + F, which folds the public E.F term
-// into party 0's first product).  One wave handles one 32 x 32 tile (blk, kt); blockIdx.z = batch.
-
-// Right side: source K x N row-major, a fragment row is a matrix column, so the 16 consecutive k a
-// lane needs are 16 strided loads whose lanes run along contiguous columns (256-byte segments).
-template <int NP>
-__global__ __launch_bounds__(256) void pack_right_kernel(PackArgs a)
-{
-    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-    const long tile = (long)blockIdx.x * 4 + wave;
-    if (tile >= (long)a.nblk * a.KT) return;
-    const int blk = (int)(tile / a.KT), kt = (int)(tile % a.KT);
-    const int b = blockIdx.z;
-    const int K = a.rows, N = a.cols;
-    const int col = blk * 32 + (lane % 32);
-    const int k0 = kt * 32 + 16 * (lane / 32);
-    const size_t mat = (size_t)K * N;
-    const size_t party_stride = (size_t)a.batch * mat;
-    auto frag = [&](int slot) -> char * {
-        return a.pack + ((((size_t)slot * a.batch + b) * a.nblk + blk) * a.KT + kt) * (kDigits * kFrag) + lane * 16;
-    };
-    u64 opened[16], first[16];
-#pragma unroll
-    for (int j = 0; j < 16; ++j) { opened[j] = 0; first[j] = 0; }
-#pragma unroll
-    for (int i = 0; i < NP; ++i) {
-        const u64 *v = a.val + (size_t)i * party_stride + (size_t)b * mat;
-        const u64 *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
-        u64 tv[16];
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            tv[j] = 0;
-            if (col < N && k0 + j < K) {
-                const size_t e = (size_t)(k0 + j) * N + col;
-                tv[j] = t[e];
-                opened[j] += v[e] - tv[j];
-            }
-        }
-        if (i == 0) {
-#pragma unroll
-            for (int j = 0; j < 16; ++j) first[j] = tv[j];
-        } else {
-#pragma unroll
-            for (int j = 0; j < 16; ++j) tv[j] = to_digits(tv[j]);
-            store_digit_rows(tv, frag(i + 1));
-        }
-    }
-    u64 w[16];
-#pragma unroll
-    for (int j = 0; j < 16; ++j) w[j] = to_digits(opened[j]);
-    store_digit_rows(w, frag(0));
-#pragma unroll
-    for (int j = 0; j < 16; ++j) w[j] = to_digits(first[j] + opened[j]);
-    store_digit_rows(w, frag(1));
-}
-
-// Left side: source M x K row-major, a fragment row is a matrix row.  Reading 16 consecutive k per
-// lane directly would make every wave-wide load touch 64 different rows; instead a wave reads its
-// tile as 4 rows x 256 contiguous bytes per load, sums the parties' shares in that layout, and turns
-// each 32 x 32 tile through LDS (rows padded to 272 bytes, conflict-free for 16-byte accesses both
-// ways) so that each lane ends up with the 16 consecutive k of one row that a fragment chunk needs.
-template <int NP, bool VEC>
-__global__ __launch_bounds__(256) void pack_left_kernel(PackArgs a)
-{
-    constexpr int kRowBytes = 272;
-    __shared__ __attribute__((aligned(16))) char turn[4][32 * kRowBytes];
-    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-    long tile = (long)blockIdx.x * 4 + wave;                // (blk, kt) pair
-    const bool active = tile < (long)a.nblk * a.KT;
-    if (!active) tile = 0;
-    const int blk = (int)(tile / a.KT), kt = (int)(tile % a.KT);
-    const int b = blockIdx.z;
-    const int M = a.rows, K = a.cols;
-    const size_t mat = (size_t)M * K;
-    const size_t party_stride = (size_t)a.batch * mat;
-    const int kk = kt * 32 + 2 * (lane % 16);               // this lane's two k of every row it loads
-    auto frag = [&](int slot) -> char * {
-        return a.pack + ((((size_t)slot * a.batch + b) * a.nblk + blk) * a.KT + kt) * (kDigits * kFrag) + lane * 16;
-    };
-    auto load2 = [&](const u64 *base, int row) -> u64x2 {  // elements (row, kk) and (row, kk+1), zero outside
-        u64x2 v = {0, 0};
-        if (row < M) {
-            const u64 *p = base + (size_t)row * K + kk;
-            if (VEC) { if (kk < K) v = *(const u64x2 *)p; }
-            else { if (kk < K) v.x = p[0]; if (kk + 1 < K) v.y = p[1]; }
-        }
-        return v;
-    };
-    // lane -> LDS: written as (row 4j + lane/16, k pair lane%16), read back as (row lane%32, k 16*(lane/32)..)
-    char *mine = turn[wave];
-    auto turn_and_store = [&](const u64x2 (&v)[8], char *dst) {
-        __syncthreads();                                    // the previous round's reads are done
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            u64x2 d = {to_digits(v[j].x), to_digits(v[j].y)};
-            *(u64x2 *)(mine + (4 * j + lane / 16) * kRowBytes + (lane % 16) * 16) = d;
-        }
-        __syncthreads();
-        u64 w[16];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            u64x2 d = *(const u64x2 *)(mine + (lane % 32) * kRowBytes + (lane / 32) * 128 + j * 16);
-            w[2 * j] = d.x; w[2 * j + 1] = d.y;
-        }
-        if (active) store_digit_rows(w, dst);
-    };
-
-    u64x2 opened[8], first[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { opened[j] = (u64x2)(0); first[j] = (u64x2)(0); }
-#pragma unroll
-    for (int i = 0; i < NP; ++i) {
-        const u64 *v = a.val + (size_t)i * party_stride + (size_t)b * mat;
-        const u64 *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
-        u64x2 tv[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int row = blk * 32 + 4 * j + lane / 16;
-            tv[j] = load2(t, row);
-            opened[j] += load2(v, row) - tv[j];
-        }
-        if (i == 0) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) first[j] = tv[j];
-        } else {
-            turn_and_store(tv, frag(i + 1));
-        }
-    }
-    turn_and_store(opened, frag(0));
-    turn_and_store(first, frag(1));
-}
 
 // ------------------------------------------------------------------ GEMM ---
 struct GemmArgs {
@@ -250,18 +64,6 @@ struct GemmShape {
     static constexpr int mfma_per_step = 36 * WM * WN;
 };
 
-// One direct-to-LDS load: 64 lanes x 16 bytes from src + lane*16 to the LDS address lds_dst + lane*16.
-// Issued through inline assembly so that the compiler's LDS-DMA bookkeeping does not serialise the
-// software pipeline; completion is awaited explicitly (wait_loads) before the workgroup barrier.
-__device__ inline void load_fragment_to_lds(const char *src, u32 lds_dst, u32 lane16)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(lane16), "s"(src), "s"(lds_dst) : "memory");
-}
-template <int N> __device__ inline void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
-__device__ inline void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-__device__ inline void workgroup_barrier() { asm volatile("s_barrier" ::: "memory"); }
-
 // Pipeline (per wave; step s covers one 32-deep k-tile of one operand pair):
 //   G(s)  12 direct-to-LDS loads of this wave's share of step s into LDS stage s % 3
 //   R(s)  24 ds_read_b128 of the wave's fragments of step s into registers
@@ -279,27 +81,9 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
     const int wm = wave / 2, wn = wave % 2;
 
-    // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tiles so
-    // that workgroups sharing an L2 also share operand fragments, and walk that range in 4-tile-tall
-    // column strips.
-    const int per_mat = g.tilesM * g.tilesN;
-    const long total = (long)per_mat * g.n * g.batch;
-    long id = blockIdx.x;
-    {
-        const long chunk = (total + 7) / 8;
-        const long full = total - (chunk - 1) * 8;       // XCDs that own `chunk` tiles (the rest own chunk-1)
-        const int xcd = (int)(id % 8);
-        const long within = id / 8;
-        id = xcd < full ? xcd * chunk + within : full * chunk + (xcd - full) * (chunk - 1) + within;
-    }
-    const int pb = (int)(id / per_mat);                  // party * batch + b
-    int t = (int)(id % per_mat);
+    const TileId tile = map_tile(blockIdx.x, g.tilesM, g.tilesN, (long)g.tilesM * g.tilesN * g.n * g.batch);
+    const int pb = tile.pb, tm = tile.tm, tn = tile.tn;
     const int party = pb / g.batch, b = pb % g.batch;
-    constexpr int GROUP = 4;
-    const int strip = t / (GROUP * g.tilesN);
-    const int strip_h = min(GROUP, g.tilesM - strip * GROUP);
-    t -= strip * GROUP * g.tilesN;
-    const int tm = strip * GROUP + t % strip_h, tn = t / strip_h;
 
     // fragment streams: step < ktn uses (E, B_i'), step >= ktn uses (A_i, F)
     const size_t slotA = (size_t)g.batch * g.nblkA * g.KT * (kDigits * kFrag);
@@ -479,7 +263,6 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
 constexpr int kWM = 2, kWN = 1;
 using Shape = GemmShape<kWM, kWN>;
 
-inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 struct Plan {
     int KT, nblkA, nblkB, tilesM, tilesN;
@@ -512,17 +295,7 @@ spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s)
     char *packA = (char *)a.workspace;
     char *packB = packA + p.packA_bytes;
 
-    PackArgs pa{a.X, a.A, packA, a.n, a.batch, a.M, a.K, p.nblkA, p.KT};
-    PackArgs pb{a.Y, a.B, packB, a.n, a.batch, a.K, a.N, p.nblkB, p.KT};
-    for_party_count(a.n, [&](auto np) {
-        constexpr int NP = decltype(np)::value;
-        KernelTimer timer(SPIN_KERNEL_PACK, s);
-        dim3 ga((unsigned)(((long)p.nblkA * p.KT + 3) / 4), 1, a.batch);
-        if (a.K % 2 == 0) pack_left_kernel<NP, true><<<ga, 256, 0, s>>>(pa);   // rows 16-byte aligned
-        else pack_left_kernel<NP, false><<<ga, 256, 0, s>>>(pa);
-        dim3 gb((unsigned)(((long)p.nblkB * p.KT + 3) / 4), 1, a.batch);
-        pack_right_kernel<NP><<<gb, 256, 0, s>>>(pb);
-    });
+    launch_pack<u64>(a, packA, packB, p.nblkA, p.nblkB, p.KT, s);
     spin_status st = check_launch("spin_beaver_matmul(pack)");
     if (st != SPIN_OK) return st;
 

@@ -1,5 +1,5 @@
 // Baseline ring GEMM on the vector ALU: Z_i = C_i + E.B_i' + A_i.F with native
-// 64-bit multiply-add, LDS-tiled (Section 6.1's design point -- native int64
+// 64-bit (or, for Z_2^128, __int128) multiply-add, LDS-tiled (Section 6.1's design point -- native int64
 // arithmetic staged through shared memory -- kept as the reference path the
 // limb-MFMA path is measured against).  B_0' = B_0 + F folds party 0's public
 // E.F term into its first product.
@@ -11,31 +11,32 @@ namespace {
 constexpr int TM = 64, TN = 64, TK = 16;   // workgroup tile; 256 threads, 4x4 outputs each
 constexpr int PADA = 2;
 
+template <class T>
 __global__ __launch_bounds__(256) void valu_gemm_kernel(int n, int batch, int M, int N, int K,
-                                                       const u64 *__restrict__ E, const u64 *__restrict__ F,
-                                                       const u64 *__restrict__ A, const u64 *__restrict__ B,
-                                                       const u64 *C, u64 *Z)
+                                                       const T *__restrict__ E, const T *__restrict__ F,
+                                                       const T *__restrict__ A, const T *__restrict__ B,
+                                                       const T *C, T *Z)
 {
-    __shared__ u64 As[TK][TM + PADA];   // k-major so that a thread's 4 rows are contiguous
-    __shared__ u64 Bs[TK][TN];
+    __shared__ T As[TK][TM + PADA];   // k-major so that a thread's 4 rows are contiguous
+    __shared__ T Bs[TK][TN];
 
     const int pb = blockIdx.z;          // party * batch + b
     const int party = pb / batch, b = pb % batch;
     const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
     const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
 
-    const u64 *Eb = E + (size_t)b * M * K;
-    const u64 *Fb = F + (size_t)b * K * N;
-    const u64 *Ai = A + (size_t)pb * M * K;
-    const u64 *Bi = B + (size_t)pb * K * N;
+    const T *Eb = E + (size_t)b * M * K;
+    const T *Fb = F + (size_t)b * K * N;
+    const T *Ai = A + (size_t)pb * M * K;
+    const T *Bi = B + (size_t)pb * K * N;
 
-    u64 acc[4][4] = {};
+    T acc[4][4] = {};
     const int ksteps = (K + TK - 1) / TK;
     for (int step = 0; step < 2 * ksteps; ++step) {
         const bool second = step >= ksteps;          // first E.B_i', then A_i.F
         const int k0 = (second ? step - ksteps : step) * TK;
-        const u64 *left = second ? Ai : Eb;
-        const u64 *right = second ? Fb : Bi;
+        const T *left = second ? Ai : Eb;
+        const T *right = second ? Fb : Bi;
         {   // left tile: 64 rows x 16 k, 4 elements per thread, stored transposed
             int row = threadIdx.x / 4, kk = (threadIdx.x % 4) * 4;
 #pragma unroll
@@ -49,7 +50,7 @@ __global__ __launch_bounds__(256) void valu_gemm_kernel(int n, int batch, int M,
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 int gk = k0 + kk, gn = n0 + col + j;
-                u64 v = 0;
+                T v = 0;
                 if (gk < K && gn < N) {
                     v = right[(size_t)gk * N + gn];
                     if (!second && party == 0) v += Fb[(size_t)gk * N + gn];
@@ -60,7 +61,7 @@ __global__ __launch_bounds__(256) void valu_gemm_kernel(int n, int batch, int M,
         __syncthreads();
 #pragma unroll
         for (int kk = 0; kk < TK; ++kk) {
-            u64 av[4], bv[4];
+            T av[4], bv[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) av[i] = As[kk][ty * 4 + i];
 #pragma unroll
@@ -72,8 +73,8 @@ __global__ __launch_bounds__(256) void valu_gemm_kernel(int n, int batch, int M,
         }
         __syncthreads();
     }
-    const u64 *Ci = C + (size_t)pb * M * N;
-    u64 *Zi = Z + (size_t)pb * M * N;
+    const T *Ci = C + (size_t)pb * M * N;
+    T *Zi = Z + (size_t)pb * M * N;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int gm = m0 + ty * 4 + i;
@@ -88,23 +89,25 @@ __global__ __launch_bounds__(256) void valu_gemm_kernel(int n, int batch, int M,
 
 }  // namespace
 
-size_t valu_workspace_bytes(int, int batch, int M, int N, int K)
+size_t valu_workspace_bytes(int, int batch, int M, int N, int K, int elem_bytes)
 {
-    return sizeof(u64) * (size_t)batch * ((size_t)M * K + (size_t)K * N);
+    return (size_t)elem_bytes * batch * ((size_t)M * K + (size_t)K * N);
 }
 
-spin_status launch_matmul_valu(const MatmulArgs &a, hipStream_t s)
+template <class T> spin_status launch_matmul_valu(const MatmulArgsT<T> &a, hipStream_t s)
 {
-    u64 *E = (u64 *)a.workspace;
-    u64 *F = E + (size_t)a.batch * a.M * a.K;
-    spin_status st = launch_open(a.X, a.A, (size_t)a.batch * a.M * a.K, a.n, E, s);
+    T *E = (T *)a.workspace;
+    T *F = E + (size_t)a.batch * a.M * a.K;
+    spin_status st = launch_open<T>(a.X, a.A, (size_t)a.batch * a.M * a.K, a.n, E, s);
     if (st != SPIN_OK) return st;
-    st = launch_open(a.Y, a.B, (size_t)a.batch * a.K * a.N, a.n, F, s);
+    st = launch_open<T>(a.Y, a.B, (size_t)a.batch * a.K * a.N, a.n, F, s);
     if (st != SPIN_OK) return st;
     KernelTimer timer(SPIN_KERNEL_GEMM_VALU, s);
     dim3 grid((a.N + TN - 1) / TN, (a.M + TM - 1) / TM, a.n * a.batch);
-    valu_gemm_kernel<<<grid, 256, 0, s>>>(a.n, a.batch, a.M, a.N, a.K, E, F, a.A, a.B, a.C, a.Z);
+    valu_gemm_kernel<T><<<grid, 256, 0, s>>>(a.n, a.batch, a.M, a.N, a.K, E, F, a.A, a.B, a.C, a.Z);
     return check_launch("spin_beaver_matmul(valu)");
 }
+template spin_status launch_matmul_valu<u64>(const MatmulArgsT<u64> &, hipStream_t);
+template spin_status launch_matmul_valu<u128>(const MatmulArgsT<u128> &, hipStream_t);
 
 }  // namespace spin

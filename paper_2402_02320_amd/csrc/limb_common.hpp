@@ -1,0 +1,304 @@
+// What the limb-decomposed GEMMs over Z_2^64 and Z_2^128 share: the balanced-digit conversion, the
+// fragment layout and the two pack kernels that open E (F) and lay all left (right) operands out as
+// int8 MFMA fragments, the direct-to-LDS load, and the mapping of workgroup ids to output tiles.
+//
+// A ring element of ND bytes (ND = 8 or 16) is rewritten as ND balanced digits s_i in [-128,127] with
+// sum_i s_i 256^i == a (mod 2^(8 ND)):  t = a + 0x80..80;  s = t ^ 0x80..80 (bytes read as int8).
+// Fragment store: [slot][batch][blk][kt][digit][1024 B]; in one 1 KiB fragment lane l's 16 bytes at
+// offset 16 l are digit d of elements (row or column 32 blk + l % 32, k = 32 kt + 16 (l / 32) + 0..15),
+// which is exactly one operand of v_mfma_i32_32x32x32_i8.  Zero padded to whole tiles.
+#pragma once
+#include "common.hpp"
+
+namespace spin {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned int u32;
+
+constexpr int kFrag = 1024;          // bytes of one 32x32 int8 fragment
+
+template <class T> __device__ inline T digit_bias();
+template <> __device__ inline u64 digit_bias<u64>() { return 0x8080808080808080ull; }
+template <> __device__ inline u128 digit_bias<u128>()
+{
+    return ((u128)0x8080808080808080ull << 64) | 0x8080808080808080ull;
+}
+template <class T> __device__ inline T to_digits(T a) { return (a + digit_bias<T>()) ^ digit_bias<T>(); }
+
+// Transposes 16 digit-words (16 elements x ND digits) into ND rows of 16 bytes and stores row p
+// (digit p of the 16 elements) at dst + p*kFrag.
+template <class T> __device__ inline void store_digit_rows(const T (&w)[16], char *dst)
+{
+#pragma unroll
+    for (int word = 0; word < (int)sizeof(T) / 4; ++word) {     // digits 4 word .. 4 word + 3
+        u32 rows[4][4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            u32 w0 = (u32)(w[4 * q + 0] >> (32 * word)), w1 = (u32)(w[4 * q + 1] >> (32 * word));
+            u32 w2 = (u32)(w[4 * q + 2] >> (32 * word)), w3 = (u32)(w[4 * q + 3] >> (32 * word));
+            // 4x4 byte transpose with v_perm_b32 (selector 0-3: second operand, 4-7: first operand)
+            u32 t0 = __builtin_amdgcn_perm(w1, w0, 0x05010400u);   // w0.b0 w1.b0 w0.b1 w1.b1
+            u32 t1 = __builtin_amdgcn_perm(w1, w0, 0x07030602u);   // w0.b2 w1.b2 w0.b3 w1.b3
+            u32 t2 = __builtin_amdgcn_perm(w3, w2, 0x05010400u);
+            u32 t3 = __builtin_amdgcn_perm(w3, w2, 0x07030602u);
+            rows[0][q] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
+            rows[1][q] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+            rows[2][q] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
+            rows[3][q] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            v4i v = {(int)rows[p][0], (int)rows[p][1], (int)rows[p][2], (int)rows[p][3]};
+            *(v4i *)(dst + (size_t)(word * 4 + p) * kFrag) = v;
+        }
+    }
+}
+
+template <class T> struct PackArgs {
+    const T *val;       // X or Y shares   [n][batch][rows][cols]
+    const T *tri;       // A or B shares   [n][batch][rows][cols]
+    char *pack;         // [n+1][batch][nblk][KT][ND][1024]
+    int n, batch;
+    int rows, cols;     // source matrix is rows x cols, row-major
+    int nblk, KT;       // blocks of 32 along the non-contracted axis; k-tiles of 32
+};
+
+// Both pack kernels make one pass over the 2n share streams of their side: the opened matrix (E or F)
+// accumulates in registers while each triple share is converted and stored as it arrives.  Slots:
+// 0 = opened, 1 + i = party i's triple share (left side A_i; right side B_i, and for party 0 B_0 + F,
+// which folds the public E.F term into party 0's first product).  One wave handles one 32 x 32 tile
+// (blk, kt); blockIdx.z = batch.  Party 0's triple share is needed again at the end (B_0 + F): 8-byte
+// rings keep it in registers, 16-byte rings read it a second time (KEEP = false) to stay within the
+// register file.
+
+// Right side: source K x N row-major, a fragment row is a matrix column, so the 16 consecutive k a
+// lane needs are 16 strided loads whose lanes run along contiguous columns.
+template <int NP, class T>
+__global__ __launch_bounds__(256) void pack_right_kernel(PackArgs<T> a)
+{
+    constexpr int ND = sizeof(T);
+    constexpr bool KEEP = sizeof(T) == 8;
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const long tile = (long)blockIdx.x * 4 + wave;
+    if (tile >= (long)a.nblk * a.KT) return;
+    const int blk = (int)(tile / a.KT), kt = (int)(tile % a.KT);
+    const int b = blockIdx.z;
+    const int K = a.rows, N = a.cols;
+    const int col = blk * 32 + (lane % 32);
+    const int k0 = kt * 32 + 16 * (lane / 32);
+    const size_t mat = (size_t)K * N;
+    const size_t party_stride = (size_t)a.batch * mat;
+    auto frag = [&](int slot) -> char * {
+        return a.pack + ((((size_t)slot * a.batch + b) * a.nblk + blk) * a.KT + kt) * (ND * kFrag) + lane * 16;
+    };
+    T opened[16], first[KEEP ? 16 : 1];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) opened[j] = 0;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        const T *v = a.val + (size_t)i * party_stride + (size_t)b * mat;
+        const T *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
+        T tv[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            tv[j] = 0;
+            if (col < N && k0 + j < K) {
+                const size_t e = (size_t)(k0 + j) * N + col;
+                tv[j] = t[e];
+                opened[j] += v[e] - tv[j];
+            }
+        }
+        if (i == 0) {
+            if (KEEP) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) first[j] = tv[j];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) tv[j] = to_digits<T>(tv[j]);
+            store_digit_rows<T>(tv, frag(i + 1));
+        }
+    }
+    T w[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) w[j] = to_digits<T>(opened[j]);
+    store_digit_rows<T>(w, frag(0));
+    const T *t0 = a.tri + (size_t)b * mat;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        T f0 = 0;
+        if (KEEP) f0 = first[j];
+        else if (col < N && k0 + j < K) f0 = t0[(size_t)(k0 + j) * N + col];
+        w[j] = to_digits<T>(f0 + opened[j]);
+    }
+    store_digit_rows<T>(w, frag(1));
+}
+
+// Left side: source M x K row-major, a fragment row is a matrix row.  Reading 16 consecutive k per
+// lane directly would make every wave-wide load touch 64 different rows; instead a wave reads its
+// tile as whole-row segments (16 bytes per lane, 32 k of one row contiguous), sums the parties'
+// shares in that layout, and turns each 32 x 32 tile through LDS (rows padded by 16 bytes,
+// conflict-free for 16-byte accesses both ways) so that each lane ends up with the 16 consecutive k
+// of one row that a fragment chunk needs.  WAVES = waves per block (LDS: WAVES x 32 padded rows).
+template <int NP, class T, bool VEC, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void pack_left_kernel(PackArgs<T> a)
+{
+    constexpr int ND = sizeof(T);
+    constexpr bool KEEP = sizeof(T) == 8;
+    constexpr int EPL = 16 / ND;                 // elements per 16-byte lane load: 2 or 1
+    constexpr int LPR = 32 / EPL;                // lanes that cover the 32 k of one row: 16 or 32
+    constexpr int RPL = 64 / LPR;                // rows per wave-wide load: 4 or 2
+    constexpr int NL = 32 / RPL;                 // loads per lane: 8 or 16
+    constexpr int kRowBytes = 32 * ND + 16;
+    struct alignas(16) Pair { T e[EPL]; };
+    __shared__ __attribute__((aligned(16))) char turn[WAVES][32 * kRowBytes];
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    long tile = (long)blockIdx.x * WAVES + wave;            // (blk, kt) pair
+    const bool active = tile < (long)a.nblk * a.KT;
+    if (!active) tile = 0;
+    const int blk = (int)(tile / a.KT), kt = (int)(tile % a.KT);
+    const int b = blockIdx.z;
+    const int M = a.rows, K = a.cols;
+    const size_t mat = (size_t)M * K;
+    const size_t party_stride = (size_t)a.batch * mat;
+    const int kk = kt * 32 + EPL * (lane % LPR);            // this lane's k (pair) of every row it loads
+    auto frag = [&](int slot) -> char * {
+        return a.pack + ((((size_t)slot * a.batch + b) * a.nblk + blk) * a.KT + kt) * (ND * kFrag) + lane * 16;
+    };
+    auto load = [&](const T *base, int row) -> Pair {       // elements (row, kk ..), zero outside
+        Pair v;
+#pragma unroll
+        for (int q = 0; q < EPL; ++q) v.e[q] = 0;
+        if (row < M) {
+            const T *p = base + (size_t)row * K + kk;
+            if (VEC) { if (kk < K) v = *(const Pair *)p; }
+            else {
+#pragma unroll
+                for (int q = 0; q < EPL; ++q) if (kk + q < K) v.e[q] = p[q];
+            }
+        }
+        return v;
+    };
+    // lane -> LDS: written as (row RPL j + lane / LPR, k position lane % LPR), read back as
+    // (row lane % 32, k 16 (lane / 32) ..)
+    char *mine = turn[wave];
+    auto turn_and_store = [&](const Pair (&v)[NL], char *dst) {
+        __syncthreads();                                    // the previous round's reads are done
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            Pair d;
+#pragma unroll
+            for (int q = 0; q < EPL; ++q) d.e[q] = to_digits<T>(v[j].e[q]);
+            *(Pair *)(mine + (RPL * j + lane / LPR) * kRowBytes + (lane % LPR) * 16) = d;
+        }
+        __syncthreads();
+        T w[16];
+#pragma unroll
+        for (int j = 0; j < 16 / EPL; ++j) {
+            Pair d = *(const Pair *)(mine + (lane % 32) * kRowBytes + (lane / 32) * (16 * ND) + j * 16);
+#pragma unroll
+            for (int q = 0; q < EPL; ++q) w[EPL * j + q] = d.e[q];
+        }
+        if (active) store_digit_rows<T>(w, dst);
+    };
+
+    Pair opened[NL], first[KEEP ? NL : 1];
+#pragma unroll
+    for (int j = 0; j < NL; ++j)
+#pragma unroll
+        for (int q = 0; q < EPL; ++q) opened[j].e[q] = 0;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        const T *v = a.val + (size_t)i * party_stride + (size_t)b * mat;
+        const T *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
+        Pair tv[NL];
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int row = blk * 32 + RPL * j + lane / LPR;
+            tv[j] = load(t, row);
+            Pair xv = load(v, row);
+#pragma unroll
+            for (int q = 0; q < EPL; ++q) opened[j].e[q] += xv.e[q] - tv[j].e[q];
+        }
+        if (i == 0) {
+            if (KEEP) {
+#pragma unroll
+                for (int j = 0; j < NL; ++j) first[j] = tv[j];
+            }
+        } else {
+            turn_and_store(tv, frag(i + 1));
+        }
+    }
+    turn_and_store(opened, frag(0));
+    if (KEEP) {
+        turn_and_store(first, frag(1));
+    } else {
+        Pair tv[NL];
+        const T *t = a.tri + (size_t)b * mat;
+#pragma unroll
+        for (int j = 0; j < NL; ++j) tv[j] = load(t, blk * 32 + RPL * j + lane / LPR);
+        turn_and_store(tv, frag(1));
+    }
+}
+
+// One direct-to-LDS load: 64 lanes x 16 bytes from src + lane*16 to the LDS address lds_dst + lane*16.
+// Issued through inline assembly so that the compiler's LDS-DMA bookkeeping does not serialise the
+// software pipeline; completion is awaited explicitly (wait_loads) before the workgroup barrier.
+__device__ inline void load_fragment_to_lds(const char *src, u32 lds_dst, u32 lane16)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(lane16), "s"(src), "s"(lds_dst) : "memory");
+}
+template <int N> __device__ inline void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
+__device__ inline void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ inline void workgroup_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// Output tile of a workgroup.  Workgroup ids are dealt round-robin to the 8 XCDs; each XCD gets a
+// contiguous range of tiles, so that workgroups sharing an L2 also share operand fragments, and walks
+// it in 4-tile-tall column strips.
+struct TileId { int pb, tm, tn; };     // party * batch + b, tile row, tile column
+__device__ inline TileId map_tile(long id, int tilesM, int tilesN, long total)
+{
+    const long chunk = (total + 7) / 8;
+    const long full = total - (chunk - 1) * 8;       // XCDs that own `chunk` tiles (the rest own chunk-1)
+    const int xcd = (int)(id % 8);
+    const long within = id / 8;
+    id = xcd < full ? xcd * chunk + within : full * chunk + (xcd - full) * (chunk - 1) + within;
+    const int per_mat = tilesM * tilesN;
+    TileId r;
+    r.pb = (int)(id / per_mat);
+    int t = (int)(id % per_mat);
+    constexpr int GROUP = 4;
+    const int strip = t / (GROUP * tilesN);
+    const int strip_h = min(GROUP, tilesM - strip * GROUP);
+    t -= strip * GROUP * tilesN;
+    r.tm = strip * GROUP + t % strip_h;
+    r.tn = t / strip_h;
+    return r;
+}
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Launches both pack kernels of one Beaver matmul (left operands from X, A; right from Y, B).
+template <class T>
+inline void launch_pack(const MatmulArgsT<T> &a, char *packA, char *packB, int nblkA, int nblkB, int KT, hipStream_t s)
+{
+    PackArgs<T> pa{a.X, a.A, packA, a.n, a.batch, a.M, a.K, nblkA, KT};
+    PackArgs<T> pb{a.Y, a.B, packB, a.n, a.batch, a.K, a.N, nblkB, KT};
+    constexpr int WAVES = sizeof(T) == 8 ? 4 : 2;
+    constexpr int EPL = 16 / sizeof(T);
+    for_party_count(a.n, [&](auto np) {
+        constexpr int NP = decltype(np)::value;
+        KernelTimer timer(SPIN_KERNEL_PACK, s);
+        dim3 ga((unsigned)(((long)nblkA * KT + WAVES - 1) / WAVES), 1, a.batch);
+        if (a.K % EPL == 0) pack_left_kernel<NP, T, true, WAVES><<<ga, 64 * WAVES, 0, s>>>(pa);   // rows 16-byte aligned
+        else pack_left_kernel<NP, T, false, WAVES><<<ga, 64 * WAVES, 0, s>>>(pa);
+        dim3 gb((unsigned)(((long)nblkB * KT + 3) / 4), 1, a.batch);
+        pack_right_kernel<NP, T><<<gb, 256, 0, s>>>(pb);
+    });
+}
+
+}  // namespace
+}  // namespace spin

@@ -103,7 +103,7 @@ size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K,
 {
     if (check_matmul_dims(n, batch, M, N, K) != SPIN_OK) return 0;
     if (path == SPIN_GEMM_LIMB_MFMA) return limb_workspace_bytes(n, batch, M, N, K);
-    if (path == SPIN_GEMM_VALU) return valu_workspace_bytes(n, batch, M, N, K);
+    if (path == SPIN_GEMM_VALU) return valu_workspace_bytes(n, batch, M, N, K, 8);
     return 0;
 }
 
