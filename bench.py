@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--path", default="limb", choices=["limb", "valu"])
-    ap.add_argument("--workload", default="matmul", choices=["matmul", "poly"],
+    ap.add_argument("--workload", default="matmul", choices=["matmul", "poly", "matmul128"],
                     help="matmul: the Beaver-matmul hot path (the benchmark); poly: completed-square polynomial "
                          "evaluation (Section 7.2 Eq. (4)) on the configuration's vector length")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -151,6 +151,49 @@ def bench_poly(args):
                       "max_abs_error_vs_2^z": err, "stream_kernels": kernels}))
 
 
+def bench_matmul128(args):
+    """Side workload: the Beaver matmul over Z_2^128 (16 digits, 136 digit pairs per ring MAC), 2048^3, 2 parties."""
+    import torch
+    from paper_2402_02320_amd import spin
+    R = spin.ring128
+    n, M = 2, 2048
+    path = spin.LIMB_MFMA if args.path == "limb" else spin.VALU
+
+    def rnd(shape):
+        return torch.empty(shape + (2,), dtype=torch.int64, device="cuda").random_(-2 ** 62, 2 ** 62)
+    X, Y, A, B, C = (rnd((n, 1, M, M)) for _ in range(5))
+    Z = torch.empty_like(C)
+    ws = torch.empty(R.beaver_matmul_workspace_bytes(n, 1, M, M, M, path), dtype=torch.uint8, device="cuda")
+    for _ in range(args.warmup):
+        R.beaver_matmul(X, Y, A, B, C, path=path, out=Z, workspace=ws)
+    torch.cuda.synchronize()
+    spin.profile_reset()
+    spin.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        R.beaver_matmul(X, Y, A, B, C, path=path, out=Z, workspace=ws)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    spin.profile_enable(False)
+    macs = 2.0 * n * M * M * M
+    key = "gemm_limb" if path == spin.LIMB_MFMA else "gemm_valu"
+    tot, cnt = spin.profile_read(key)
+    pk, pc = spin.profile_read("pack")
+    spin.profile_reset()
+    gemm_ms = tot / cnt
+    roof = None
+    if path == spin.LIMB_MFMA:
+        ach = macs * 272 / (cnt / args.steps) / (gemm_ms * 1e-3) / 1e12      # 136 digit pairs x 2 ops
+        roof = {"bound": "mfma", "kernel": "limb128_gemm_kernel", "achieved": ach, "peak": PEAK_INT8_TOPS,
+                "unit": "TOP/s", "frac": ach / PEAK_INT8_TOPS, "traffic": None, "avg_launch_ms": gemm_ms}
+    print(json.dumps({"metric": "Z_2^128 ring MACs/s for Beaver matmul (side workload)", "value": macs / (ms * 1e-3),
+                      "unit": "ring MAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+                      "higher_is_better": True, "vs_baseline": None, "dtype": "u128 (int8 digits, int32 accumulate)"
+                      if path == spin.LIMB_MFMA else "u128", "data": "synthetic",
+                      "config": {"workload": "2 parties, M=N=K=2048 over Z_2^128", "gemm_path": args.path},
+                      "roofline": roof, "gemm_avg_ms": gemm_ms, "pack_avg_ms": pk / pc if pc else None}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -168,6 +211,8 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "poly":
         return bench_poly(args)
+    if args.workload == "matmul128":
+        return bench_matmul128(args)
     c = workloads.CONFIGS[args.config]
     g = c.gemms[0]
     n, f = c.n, c.f

@@ -151,6 +151,32 @@ spin_status spin_beaver_and(int n, size_t count,
                             const uint64_t *a, const uint64_t *b, const uint64_t *c,
                             uint64_t *z, spin_stream stream);
 
+/* The same calls over the ring Z_2^128 (the paper's second ring width, Section 6: "64-bit or
+ * 128-bit"; its own kernels multiply __int128, Section 6.1).  A ring element is 16 bytes,
+ * little-endian: two uint64_t words, low word first (the layout of unsigned __int128).  Pointers
+ * are passed as uint64_t* to those words; `count` and the matrix dimensions count ring elements;
+ * tensors are party-major as before.  A 128-bit generator word is the pair of 64-bit generator
+ * outputs at indices 2k (low) and 2k+1 (high).  spin128_trunc: Truncate(x,f) =
+ * UnsignedTruncate(x + 2^126, 128, f) - 2^(126-f), tuple fields r_top = bits f..126 and
+ * r_msb = bit 127 of r, 1 <= f <= 125.  Everything else as documented at the 64-bit call.       */
+spin_status spin128_share(const uint64_t *x, size_t count, int n, uint64_t seed, uint64_t stream_id,
+                          uint64_t *shares, spin_stream stream);
+spin_status spin128_open(const uint64_t *shares, const uint64_t *mask, size_t count, int n,
+                         uint64_t *out, spin_stream stream);
+spin_status spin128_beaver_matmul(int n, int batch, int M, int N, int K,
+                                  const uint64_t *X, const uint64_t *Y,
+                                  const uint64_t *A, const uint64_t *B, const uint64_t *C,
+                                  uint64_t *Z, spin_gemm_path path,
+                                  void *workspace, size_t workspace_bytes, spin_stream stream);
+size_t spin128_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path);
+spin_status spin128_beaver_mul(int n, size_t count,
+                               const uint64_t *x, const uint64_t *y,
+                               const uint64_t *a, const uint64_t *b, const uint64_t *c,
+                               uint64_t *z, spin_stream stream);
+spin_status spin128_trunc(int n, size_t count, int f, const uint64_t *x,
+                          const uint64_t *r, const uint64_t *r_top, const uint64_t *r_msb,
+                          uint64_t *out, spin_stream stream);
+
 /* Per-kernel timing for benchmarks (measurement aid, not part of the protocol).
  * While enabled, every kernel the library launches is bracketed by a pair of
  * HIP events recorded on the caller's stream; events are created on demand

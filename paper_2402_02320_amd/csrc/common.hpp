@@ -95,5 +95,7 @@ size_t valu_workspace_bytes(int n, int batch, int M, int N, int K, int elem_byte
 template <class T> spin_status launch_matmul_valu(const MatmulArgsT<T> &a, hipStream_t s);
 size_t limb_workspace_bytes(int n, int batch, int M, int N, int K);
 spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s);
+size_t limb128_workspace_bytes(int n, int batch, int M, int N, int K);
+spin_status launch_matmul_limb128(const MatmulArgs128 &a, hipStream_t s);
 
 }  // namespace spin

@@ -209,7 +209,10 @@ __global__ __launch_bounds__(64 * WAVES) void pack_left_kernel(PackArgs<T> a)
     for (int j = 0; j < NL; ++j)
 #pragma unroll
         for (int q = 0; q < EPL; ++q) opened[j].e[q] = 0;
-#pragma unroll
+    // 16-byte rings keep the party loop rolled: unrolled, the loads of all parties are hoisted to the
+    // top and the live values exceed the register file
+    constexpr int kPartyUnroll = KEEP ? NP : 1;
+#pragma unroll kPartyUnroll
     for (int i = 0; i < NP; ++i) {
         const T *v = a.val + (size_t)i * party_stride + (size_t)b * mat;
         const T *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
@@ -223,7 +226,7 @@ __global__ __launch_bounds__(64 * WAVES) void pack_left_kernel(PackArgs<T> a)
             for (int q = 0; q < EPL; ++q) opened[j].e[q] += xv.e[q] - tv[j].e[q];
         }
         if (i == 0) {
-            if (KEEP) {
+            if constexpr (KEEP) {
 #pragma unroll
                 for (int j = 0; j < NL; ++j) first[j] = tv[j];
             }
@@ -232,7 +235,7 @@ __global__ __launch_bounds__(64 * WAVES) void pack_left_kernel(PackArgs<T> a)
         }
     }
     turn_and_store(opened, frag(0));
-    if (KEEP) {
+    if constexpr (KEEP) {
         turn_and_store(first, frag(1));
     } else {
         Pair tv[NL];

@@ -216,6 +216,72 @@ spin_status spin_lincomb_trunc(int n, size_t count, int terms, const uint64_t *c
     return launch_lincomb_trunc(n, count, t, constant, f, r, r_top, r_msb, out, (hipStream_t)stream);
 }
 
+// ---- Z_2^128 --------------------------------------------------------------------------------------
+static inline const u128 *r128(const uint64_t *p) { return (const u128 *)p; }
+static inline u128 *r128(uint64_t *p) { return (u128 *)p; }
+
+spin_status spin128_share(const uint64_t *x, size_t count, int n, uint64_t seed, uint64_t stream_id,
+                          uint64_t *shares, spin_stream stream)
+{
+    if (bad_ptr(x) || bad_ptr(shares) || bad_n(n) || count == 0) return SPIN_EINVAL;
+    if (count > kMaxCount / 2) return SPIN_ERANGE;
+    PartyKeys keys;
+    for (int i = 0; i < SPIN_MAX_PARTIES; ++i) keys.key[i] = stream_key(seed, stream_id, (u64)i);
+    return launch_share128(r128(x), count, n, keys, r128(shares), (hipStream_t)stream);
+}
+
+spin_status spin128_open(const uint64_t *shares, const uint64_t *mask, size_t count, int n, uint64_t *out,
+                         spin_stream stream)
+{
+    if (bad_ptr(shares) || bad_ptr(out) || (mask && !aligned16(mask)) || bad_n(n) || count == 0)
+        return SPIN_EINVAL;
+    if (count > kMaxCount / 2) return SPIN_ERANGE;
+    return launch_open<u128>(r128(shares), r128(mask), count, n, r128(out), (hipStream_t)stream);
+}
+
+size_t spin128_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path)
+{
+    if (check_matmul_dims(n, batch, M, N, K) != SPIN_OK) return 0;
+    if (path == SPIN_GEMM_LIMB_MFMA) return limb128_workspace_bytes(n, batch, M, N, K);
+    if (path == SPIN_GEMM_VALU) return valu_workspace_bytes(n, batch, M, N, K, 16);
+    return 0;
+}
+
+spin_status spin128_beaver_matmul(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Y,
+                                  const uint64_t *A, const uint64_t *B, const uint64_t *C, uint64_t *Z,
+                                  spin_gemm_path path, void *workspace, size_t workspace_bytes, spin_stream stream)
+{
+    if (bad_ptr(X) || bad_ptr(Y) || bad_ptr(A) || bad_ptr(B) || bad_ptr(C) || bad_ptr(Z)) return SPIN_EINVAL;
+    if (path != SPIN_GEMM_LIMB_MFMA && path != SPIN_GEMM_VALU) return SPIN_EINVAL;
+    spin_status st = check_matmul_dims(n, batch, M, N, K);
+    if (st != SPIN_OK) return st;
+    const size_t need = spin128_beaver_matmul_workspace_bytes(n, batch, M, N, K, path);
+    if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need)
+        return SPIN_EWORKSPACE;
+    MatmulArgs128 a{n, batch, M, N, K, r128(X), r128(Y), r128(A), r128(B), r128(C), r128(Z), workspace};
+    return path == SPIN_GEMM_LIMB_MFMA ? launch_matmul_limb128(a, (hipStream_t)stream)
+                                       : launch_matmul_valu<u128>(a, (hipStream_t)stream);
+}
+
+spin_status spin128_beaver_mul(int n, size_t count, const uint64_t *x, const uint64_t *y, const uint64_t *a,
+                               const uint64_t *b, const uint64_t *c, uint64_t *z, spin_stream stream)
+{
+    if (bad_ptr(x) || bad_ptr(y) || bad_ptr(a) || bad_ptr(b) || bad_ptr(c) || bad_ptr(z) || bad_n(n) || count == 0)
+        return SPIN_EINVAL;
+    if (count > kMaxCount / 2) return SPIN_ERANGE;
+    return launch_beaver_mul<u128>(n, count, r128(x), r128(y), r128(a), r128(b), r128(c), r128(z), (hipStream_t)stream);
+}
+
+spin_status spin128_trunc(int n, size_t count, int f, const uint64_t *x, const uint64_t *r, const uint64_t *r_top,
+                          const uint64_t *r_msb, uint64_t *out, spin_stream stream)
+{
+    if (bad_ptr(x) || bad_ptr(r) || bad_ptr(r_top) || bad_ptr(r_msb) || bad_ptr(out) || bad_n(n) || count == 0)
+        return SPIN_EINVAL;
+    if (f < 1 || f > 125) return SPIN_EINVAL;
+    if (count > kMaxCount / 2) return SPIN_ERANGE;
+    return launch_trunc<u128>(n, count, f, r128(x), r128(r), r128(r_top), r128(r_msb), r128(out), (hipStream_t)stream);
+}
+
 const char *spin_status_string(spin_status status)
 {
     switch (status) {

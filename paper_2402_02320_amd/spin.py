@@ -53,6 +53,15 @@ def lib():
         L.spin_profile_reset.restype = None
         L.spin_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_uint)]
         L.spin_profile_read.restype = i32
+        L.spin128_share.argtypes = L.spin_share.argtypes
+        L.spin128_open.argtypes = L.spin_open.argtypes
+        L.spin128_beaver_matmul.argtypes = L.spin_beaver_matmul.argtypes
+        L.spin128_beaver_matmul_workspace_bytes.argtypes = L.spin_beaver_matmul_workspace_bytes.argtypes
+        L.spin128_beaver_matmul_workspace_bytes.restype = sz
+        L.spin128_beaver_mul.argtypes = L.spin_beaver_mul.argtypes
+        L.spin128_trunc.argtypes = L.spin_trunc.argtypes
+        for name in ("spin128_share", "spin128_open", "spin128_beaver_matmul", "spin128_beaver_mul", "spin128_trunc"):
+            getattr(L, name).restype = i32
         L.spin_status_string.argtypes = [i32]
         L.spin_status_string.restype = ctypes.c_char_p
         L.spin_last_hip_error.restype = ctypes.c_char_p
@@ -202,6 +211,74 @@ def lincomb_trunc(terms, coefs, constant=0, f=0, tuple_=None, out=None):
     _check(lib().spin_lincomb_trunc(n, terms[0][0].numel(), len(terms), ptrs, cf, int(constant) % (1 << 64), f,
                                     r, rt, rm, _dev(out, "out"), _stream()))
     return out
+
+
+class ring128:
+    """The same calls over Z_2^128.  A ring tensor of shape S is a torch.int64 tensor of shape S + (2,):
+    two 64-bit words per element, low word first."""
+
+    @staticmethod
+    def _elems(t):
+        if t.shape[-1] != 2:
+            raise SpinError("128-bit ring tensors carry a trailing axis of 2 words")
+        return t.numel() // 2
+
+    @staticmethod
+    def share(x, n, seed, stream_id, out=None):
+        if out is None:
+            out = torch.empty((n,) + tuple(x.shape), dtype=torch.int64, device=x.device)
+        _check(lib().spin128_share(_dev(x, "x"), ring128._elems(x), n, seed, stream_id, _dev(out, "shares"), _stream()))
+        return out
+
+    @staticmethod
+    def open(shares, mask=None, out=None):  # noqa: A003
+        n = shares.shape[0]
+        if out is None:
+            out = torch.empty(tuple(shares.shape[1:]), dtype=torch.int64, device=shares.device)
+        _check(lib().spin128_open(_dev(shares, "shares"), None if mask is None else _dev(mask, "mask"),
+                                  ring128._elems(out), n, _dev(out, "out"), _stream()))
+        return out
+
+    @staticmethod
+    def beaver_matmul_workspace_bytes(n, batch, M, N, K, path=LIMB_MFMA):
+        return int(lib().spin128_beaver_matmul_workspace_bytes(n, batch, M, N, K, path))
+
+    @staticmethod
+    def beaver_matmul(X, Y, A, B, C, path=LIMB_MFMA, out=None, workspace=None):
+        n, batch, M, K, _ = X.shape
+        N = Y.shape[3]
+        if tuple(Y.shape) != (n, batch, K, N, 2) or A.shape != X.shape or B.shape != Y.shape \
+                or tuple(C.shape) != (n, batch, M, N, 2):
+            raise SpinError("inconsistent operand shapes")
+        if out is None:
+            out = torch.empty_like(C)
+        need = ring128.beaver_matmul_workspace_bytes(n, batch, M, N, K, path)
+        if need == 0:
+            raise SpinError("invalid matmul dimensions")
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+        _check(lib().spin128_beaver_matmul(n, batch, M, N, K, _dev(X, "X"), _dev(Y, "Y"), _dev(A, "A"), _dev(B, "B"),
+                                           _dev(C, "C"), _dev(out, "Z"), path, workspace.data_ptr(),
+                                           workspace.numel() * workspace.element_size(), _stream()))
+        return out
+
+    @staticmethod
+    def beaver_mul(x, y, a, b, c, out=None):
+        n = x.shape[0]
+        if out is None:
+            out = torch.empty_like(x)
+        _check(lib().spin128_beaver_mul(n, ring128._elems(x[0]), _dev(x, "x"), _dev(y, "y"), _dev(a, "a"),
+                                        _dev(b, "b"), _dev(c, "c"), _dev(out, "z"), _stream()))
+        return out
+
+    @staticmethod
+    def trunc(x, r, r_top, r_msb, f, out=None):
+        n = x.shape[0]
+        if out is None:
+            out = torch.empty_like(x)
+        _check(lib().spin128_trunc(n, ring128._elems(x[0]), f, _dev(x, "x"), _dev(r, "r"), _dev(r_top, "r_top"),
+                                   _dev(r_msb, "r_msb"), _dev(out, "out"), _stream()))
+        return out
 
 
 KERNELS = {"random": 0, "share": 1, "open": 2, "beaver_mul": 3, "trunc": 4, "pack": 5, "gemm_limb": 6,
