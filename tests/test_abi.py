@@ -21,7 +21,7 @@ def L():
 def declared_symbols():
     text = open(os.path.join(ROOT, "include", "spin.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(spin_[a-z0-9_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(spin[0-9]*_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_declares_the_five_calls():
@@ -31,7 +31,10 @@ def test_header_declares_the_five_calls():
 
 
 def test_every_declared_symbol_is_exported(L):
-    for name in declared_symbols():
+    names = declared_symbols()
+    for expected in ("spin128_beaver_matmul", "spin_bshare", "spin_lincomb_trunc", "spin_profile_read"):
+        assert expected in names
+    for name in names:
         assert getattr(L, name) is not None
 
 
@@ -69,6 +72,25 @@ def test_workspace_query(L):
     got = q(5, 1, 4096, 4096, 4096, 0)
     assert got == 8 * 6 * (4096 * 4096 * 2)
     assert q(3, 1, 64, 64, 64, 0) >= 8 * 4 * (64 * 64 * 2)
+
+
+def test_validation_of_the_wider_entry_points(L):
+    fake = ctypes.c_void_p(0x1000)
+    EINVAL, EWORKSPACE = 1, 3
+    assert L.spin128_trunc(2, 8, 126, fake, fake, fake, fake, fake, None) == EINVAL
+    assert L.spin128_trunc(2, 8, 0, fake, fake, fake, fake, fake, None) == EINVAL
+    assert L.spin128_share(fake, 8, 9, 1, 1, fake, None) == EINVAL
+    assert L.spin128_beaver_matmul(2, 1, 4, 4, 4, fake, fake, fake, fake, fake, fake, 0, None, 0, None) == EWORKSPACE
+    q = L.spin128_beaver_matmul_workspace_bytes
+    assert q(3, 2, 10, 7, 5, 1) == 16 * 2 * (10 * 5 + 5 * 7)
+    assert q(2, 1, 2048, 2048, 2048, 0) == 16 * 3 * (2048 * 2048 * 2)
+    assert L.spin_beaver_and(2, 8, fake, fake, fake, fake, None, fake, None) == EINVAL
+    assert L.spin_bopen(fake, None, 0, 2, fake, None) == EINVAL
+    ptrs = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    coef = (ctypes.c_uint64 * 2)(1, 2)
+    assert L.spin_lincomb_trunc(2, 8, 9, ptrs, coef, 0, 0, None, None, None, fake, None) == EINVAL
+    assert L.spin_lincomb_trunc(2, 8, 2, ptrs, coef, 0, 16, None, None, None, fake, None) == EINVAL
+    assert L.spin_lincomb_trunc(2, 8, 2, None, coef, 0, 0, None, None, None, fake, None) == EINVAL
 
 
 def test_status_strings(L):

@@ -267,3 +267,29 @@ def test_paths_agree_on_config5_shape_slice():
     z0 = spin.beaver_matmul(X, Y, A, B, C, path=spin.LIMB_MFMA)
     z1 = spin.beaver_matmul(X, Y, A, B, C, path=spin.VALU)
     assert torch.equal(z0, z1)
+
+
+def test_calls_run_on_the_callers_stream():
+    # the whole path enqueued on a side stream, with no synchronisation until the end: every call must be
+    # ordered on that stream (a kernel launched on another stream would read unfinished inputs)
+    rng = np.random.default_rng(77)
+    n, M, N, K, f = 3, 257, 130, 96, 16
+    x = rng.integers(-(1 << 20), 1 << 20, size=(1, M, K), dtype=np.int64).view(np.uint64)
+    y = rng.integers(-(1 << 20), 1 << 20, size=(1, K, N), dtype=np.int64).view(np.uint64)
+    A, B, C = oracle.dealer_matmul(n, 1, M, N, K, seed=78)
+    r, rt, rm = oracle.trunc_dealer(n, M * N, f, seed=78)
+    xd, yd, Ad, Bd, Cd, rd, rtd, rmd = map(dev, (x, y, A, B, C, r, rt, rm))
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for path in (spin.LIMB_MFMA, spin.VALU):
+            Xs = spin.share(xd, n, 78, oracle.STREAM_X)
+            Ys = spin.share(yd, n, 78, oracle.STREAM_Y)
+            Z = spin.beaver_matmul(Xs, Ys, Ad, Bd, Cd, path=path)
+            T = spin.trunc(Z.view(n, -1), rd, rtd, rmd, f)
+            out = spin.open(T)
+    side.synchronize()
+    X, Y = oracle.share(x, n, 78, oracle.STREAM_X), oracle.share(y, n, 78, oracle.STREAM_Y)
+    Zo = oracle.beaver_matmul(X, Y, A, B, C)
+    To = oracle.trunc(Zo.reshape(n, -1), r, rt, rm, f)
+    assert (host(T) == To).all() and (host(out) == oracle.open_(To)).all()
