@@ -17,6 +17,22 @@ namespace {
 
 constexpr int kBlock = 256;
 
+// Streaming accesses.  Tensors far larger than the caches are read and written exactly once, and
+// non-temporal loads and stores (no cache retention) measured 14 % faster on the 25-stream truncation
+// pattern (n = 5, 2^24 elements, same process: 6.4 against 5.6 TB/s).
+// Small tensors keep ordinary accesses so that the next kernel finds them in L2 / Infinity Cache.
+constexpr size_t kStreamingBytes = (size_t)64 << 20;    // per call, all parties together
+template <bool NT, class V> __device__ inline V ld(const V *p)
+{
+    if constexpr (NT && !std::is_same<V, u128>::value) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+template <bool NT, class V> __device__ inline void st(V *p, V v)
+{
+    if constexpr (NT && !std::is_same<V, u128>::value) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
 // V = u64x2 (two ring elements per lane) or u64 (odd counts, whose party rows
 // are only 8-byte aligned).
 template <class V> struct Lanes;
@@ -46,24 +62,24 @@ __global__ __launch_bounds__(kBlock) void random_kernel(V *__restrict__ out, siz
 }
 
 // shares[i] = generator output for i >= 1, shares[0] = x - sum of the others (Section 4.1).
-template <int NP, class V>
+template <int NP, class V, bool NT>
 __global__ __launch_bounds__(kBlock) void share_kernel(const V *__restrict__ x, size_t nvec, PartyKeys keys,
                                                       V *__restrict__ shares)
 {
     size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (v >= nvec) return;
-    V rest = x[v];
+    V rest = ld<NT>(x + v);
 #pragma unroll
     for (int i = 1; i < NP; ++i) {
         V s = gen<V>(keys.key[i], v * Lanes<V>::width);
-        shares[(size_t)i * nvec + v] = s;
+        st<NT>(shares + (size_t)i * nvec + v, s);
         rest -= s;
     }
-    shares[v] = rest;
+    st<NT>(shares + v, rest);
 }
 
 // out = sum_i (shares_i - mask_i): the party-axis reduction that replaces the network exchange.
-template <int NP, bool MASK, class T>
+template <int NP, bool MASK, class T, bool NT>
 __global__ __launch_bounds__(kBlock) void open_kernel(const T *__restrict__ shares, const T *__restrict__ mask,
                                                      size_t count, T *__restrict__ out)
 {
@@ -72,18 +88,18 @@ __global__ __launch_bounds__(kBlock) void open_kernel(const T *__restrict__ shar
     T s[NP], m[NP];
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
-        s[i] = shares[(size_t)i * count + v];
-        if (MASK) m[i] = mask[(size_t)i * count + v];
+        s[i] = ld<NT>(shares + (size_t)i * count + v);
+        if (MASK) m[i] = ld<NT>(mask + (size_t)i * count + v);
     }
     T acc = 0;
 #pragma unroll
     for (int i = 0; i < NP; ++i) acc += MASK ? s[i] - m[i] : s[i];
-    out[v] = acc;
+    st<NT>(out + v, acc);
 }
 
 // z_i = c_i + e*b_i + a_i*f (+ e*f for party 0) with e, f opened in registers (Section 4.3).
 // z may alias an input: a thread reads all of its inputs before it writes.
-template <int NP, class T>
+template <int NP, class T, bool NT>
 __global__ __launch_bounds__(kBlock) void beaver_mul_kernel(const T *x, const T *y, const T *a, const T *b,
                                                            const T *c, size_t count, T *z)
 {
@@ -93,7 +109,8 @@ __global__ __launch_bounds__(kBlock) void beaver_mul_kernel(const T *x, const T 
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
         size_t o = (size_t)i * count + v;
-        xv[i] = x[o]; yv[i] = y[o]; av[i] = a[o]; bv[i] = b[o]; cv[i] = c[o];
+        xv[i] = ld<NT>(x + o); yv[i] = ld<NT>(y + o); av[i] = ld<NT>(a + o); bv[i] = ld<NT>(b + o);
+        cv[i] = ld<NT>(c + o);
     }
     T e = 0, f = 0;
 #pragma unroll
@@ -102,13 +119,13 @@ __global__ __launch_bounds__(kBlock) void beaver_mul_kernel(const T *x, const T 
     for (int i = 0; i < NP; ++i) {
         T bi = bv[i];
         if (i == 0) bi += f;                       // folds the public e*f into party 0's term
-        z[(size_t)i * count + v] = cv[i] + e * bi + av[i] * f;
+        st<NT>(z + (size_t)i * count + v, cv[i] + e * bi + av[i] * f);
     }
 }
 
 // The combine of the signed probabilistic truncation (Section 4.4) on party shares y[] held in
 // registers; steps as listed at spin_trunc in include/spin.h.
-template <int NP, class T>
+template <int NP, class T, bool NT>
 __device__ inline void truncate_and_store(const T (&y)[NP], const T *__restrict__ r, const T *__restrict__ r_top,
                                           const T *__restrict__ r_msb, size_t count, size_t v, int f, T *out)
 {
@@ -118,8 +135,8 @@ __device__ inline void truncate_and_store(const T (&y)[NP], const T *__restrict_
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
         size_t o = (size_t)i * count + v;
-        rt[i] = r_top[o]; rm[i] = r_msb[o];
-        c += y[i] + r[o];
+        rt[i] = ld<NT>(r_top + o); rm[i] = ld<NT>(r_msb + o);
+        c += y[i] + ld<NT>(r + o);
     }
     const T topmask = (((T)1 << (L - 1 - f)) - 1);
     const T c_msb = c >> (L - 1);
@@ -129,11 +146,11 @@ __device__ inline void truncate_and_store(const T (&y)[NP], const T *__restrict_
         T b = rm[i] - 2 * c_msb * rm[i];
         T o = (b << (L - 1 - f)) - rt[i];
         if (i == 0) o += (c_msb << (L - 1 - f)) + c_top - ((T)1 << (L - 2 - f));
-        out[(size_t)i * count + v] = o;
+        st<NT>(out + (size_t)i * count + v, o);
     }
 }
 
-template <int NP, class T>
+template <int NP, class T, bool NT>
 __global__ __launch_bounds__(kBlock) void trunc_kernel(const T *x, const T *__restrict__ r,
                                                       const T *__restrict__ r_top, const T *__restrict__ r_msb,
                                                       size_t count, int f, T *out)
@@ -142,14 +159,14 @@ __global__ __launch_bounds__(kBlock) void trunc_kernel(const T *x, const T *__re
     if (v >= count) return;
     T y[NP];
 #pragma unroll
-    for (int i = 0; i < NP; ++i) y[i] = x[(size_t)i * count + v];
-    truncate_and_store<NP, T>(y, r, r_top, r_msb, count, v, f, out);
+    for (int i = 0; i < NP; ++i) y[i] = ld<NT>(x + (size_t)i * count + v);
+    truncate_and_store<NP, T, NT>(y, r, r_top, r_msb, count, v, f, out);
 }
 
 // y_i = sum_j coef_j in_j,i (+ constant for party 0), then the truncation above when TRUNC
 // (Section 4.3 Addition/Scaling; Section 4.4 Polynomial evaluation: one deferred truncation).
 // The term loop is a run-time loop; every iteration issues one load per party.
-template <int NP, bool TRUNC>
+template <int NP, bool TRUNC, bool NT>
 __global__ __launch_bounds__(kBlock) void lincomb_trunc_kernel(LincombTerms t, u64 constant, const u64 *__restrict__ r,
                                                               const u64 *__restrict__ r_top,
                                                               const u64 *__restrict__ r_msb, size_t count, int f,
@@ -164,13 +181,13 @@ __global__ __launch_bounds__(kBlock) void lincomb_trunc_kernel(LincombTerms t, u
         const u64 *src = t.in[j];
         const u64 cf = t.coef[j];
 #pragma unroll
-        for (int i = 0; i < NP; ++i) y[i] += cf * src[(size_t)i * count + v];
+        for (int i = 0; i < NP; ++i) y[i] += cf * ld<NT>(src + (size_t)i * count + v);
     }
     if (TRUNC) {
-        truncate_and_store<NP, u64>(y, r, r_top, r_msb, count, v, f, out);
+        truncate_and_store<NP, u64, NT>(y, r, r_top, r_msb, count, v, f, out);
     } else {
 #pragma unroll
-        for (int i = 0; i < NP; ++i) out[(size_t)i * count + v] = y[i];
+        for (int i = 0; i < NP; ++i) st<NT>(out + (size_t)i * count + v, y[i]);
     }
 }
 
@@ -234,6 +251,13 @@ __global__ __launch_bounds__(kBlock) void beaver_and_kernel(const u64 *x, const 
 
 inline unsigned grid_for(size_t n) { return (unsigned)((n + kBlock - 1) / kBlock); }
 
+// Calls fn(std::true_type) for calls that stream more than the caches hold, fn(std::false_type) otherwise.
+template <class F> inline void for_streaming(size_t bytes, F &&fn)
+{
+    if (bytes >= kStreamingBytes) fn(std::true_type());
+    else fn(std::false_type());
+}
+
 }  // namespace
 
 spin_status launch_random(u64 *out, size_t count, u64 key, u64 first_idx, hipStream_t s)
@@ -251,11 +275,13 @@ spin_status launch_share(const u64 *x, size_t count, int n, const PartyKeys &key
     KernelTimer timer(SPIN_KERNEL_SHARE, s);
     for_party_count(n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
+        // ordinary stores: in a pipeline the shares are read again at once (by the pack kernels), and
+        // non-temporal stores, although faster in isolation, measured slower there
         if (count % 2 == 0)
-            share_kernel<NP, u64x2><<<grid_for(count / 2), kBlock, 0, s>>>((const u64x2 *)x, count / 2, keys,
-                                                                          (u64x2 *)shares);
+            share_kernel<NP, u64x2, false><<<grid_for(count / 2), kBlock, 0, s>>>((const u64x2 *)x, count / 2, keys,
+                                                                                 (u64x2 *)shares);
         else
-            share_kernel<NP, u64><<<grid_for(count), kBlock, 0, s>>>(x, count, keys, shares);
+            share_kernel<NP, u64, false><<<grid_for(count), kBlock, 0, s>>>(x, count, keys, shares);
     });
     return check_launch("spin_share");
 }
@@ -266,8 +292,11 @@ spin_status launch_open(const T *shares, const T *mask, size_t count, int n, T *
     KernelTimer timer(SPIN_KERNEL_OPEN, s);
     for_party_count(n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
-        if (mask) open_kernel<NP, true, T><<<grid_for(count), kBlock, 0, s>>>(shares, mask, count, out);
-        else open_kernel<NP, false, T><<<grid_for(count), kBlock, 0, s>>>(shares, nullptr, count, out);
+        for_streaming((size_t)n * count * sizeof(T), [&](auto nt) {
+            constexpr bool NT = decltype(nt)::value;
+            if (mask) open_kernel<NP, true, T, NT><<<grid_for(count), kBlock, 0, s>>>(shares, mask, count, out);
+            else open_kernel<NP, false, T, NT><<<grid_for(count), kBlock, 0, s>>>(shares, nullptr, count, out);
+        });
     });
     return check_launch("spin_open");
 }
@@ -278,7 +307,10 @@ spin_status launch_beaver_mul(int n, size_t count, const T *x, const T *y, const
 {
     KernelTimer timer(SPIN_KERNEL_BEAVER_MUL, s);
     for_party_count(n, [&](auto np) {
-        beaver_mul_kernel<decltype(np)::value, T><<<grid_for(count), kBlock, 0, s>>>(x, y, a, b, c, count, z);
+        for_streaming((size_t)n * count * sizeof(T), [&](auto nt) {
+            beaver_mul_kernel<decltype(np)::value, T, decltype(nt)::value><<<grid_for(count), kBlock, 0, s>>>(
+                x, y, a, b, c, count, z);
+        });
     });
     return check_launch("spin_beaver_mul");
 }
@@ -289,7 +321,10 @@ spin_status launch_trunc(int n, size_t count, int f, const T *x, const T *r, con
 {
     KernelTimer timer(SPIN_KERNEL_TRUNC, s);
     for_party_count(n, [&](auto np) {
-        trunc_kernel<decltype(np)::value, T><<<grid_for(count), kBlock, 0, s>>>(x, r, r_top, r_msb, count, f, out);
+        for_streaming((size_t)n * count * sizeof(T), [&](auto nt) {
+            trunc_kernel<decltype(np)::value, T, decltype(nt)::value><<<grid_for(count), kBlock, 0, s>>>(
+                x, r, r_top, r_msb, count, f, out);
+        });
     });
     return check_launch("spin_trunc");
 }
@@ -298,7 +333,7 @@ spin_status launch_share128(const u128 *x, size_t count, int n, const PartyKeys 
 {
     KernelTimer timer(SPIN_KERNEL_SHARE, s);
     for_party_count(n, [&](auto np) {
-        share_kernel<decltype(np)::value, u128><<<grid_for(count), kBlock, 0, s>>>(x, count, keys, shares);
+        share_kernel<decltype(np)::value, u128, false><<<grid_for(count), kBlock, 0, s>>>(x, count, keys, shares);
     });
     return check_launch("spin128_share");
 }
@@ -350,12 +385,15 @@ spin_status launch_lincomb_trunc(int n, size_t count, const LincombTerms &t, u64
     KernelTimer timer(SPIN_KERNEL_LINCOMB, s);
     for_party_count(n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
-        if (f > 0)
-            lincomb_trunc_kernel<NP, true><<<grid_for(count), kBlock, 0, s>>>(t, constant, r, r_top, r_msb, count, f,
-                                                                             out);
-        else
-            lincomb_trunc_kernel<NP, false><<<grid_for(count), kBlock, 0, s>>>(t, constant, nullptr, nullptr, nullptr,
-                                                                              count, 0, out);
+        for_streaming((size_t)n * count * sizeof(u64), [&](auto nt) {
+            constexpr bool NT = decltype(nt)::value;
+            if (f > 0)
+                lincomb_trunc_kernel<NP, true, NT><<<grid_for(count), kBlock, 0, s>>>(t, constant, r, r_top, r_msb,
+                                                                                     count, f, out);
+            else
+                lincomb_trunc_kernel<NP, false, NT><<<grid_for(count), kBlock, 0, s>>>(t, constant, nullptr, nullptr,
+                                                                                      nullptr, count, 0, out);
+        });
     });
     return check_launch("spin_lincomb_trunc");
 }

@@ -77,6 +77,32 @@ def test_trunc(n, f, count):
     assert (host(Xd) == want).all()
 
 
+# Past 64 MB per call the many-stream kernels switch to non-temporal loads and stores; both the paired
+# (even count) and the single-word (odd count) forms of that variant are compared here.
+@pytest.mark.parametrize("n,count", [(5, (1 << 21) + 2), (3, (3 << 20) + 1), (8, 1 << 20)])
+def test_streaming_variants_of_open_mul_trunc(n, count):
+    assert n * count * 8 >= 64 << 20
+    rng = np.random.default_rng(n + count)
+    f = 16
+    xs = rng.integers(-(1 << 40), 1 << 40, size=count, dtype=np.int64).view(np.uint64)
+    ys = rng.integers(-(1 << 20), 1 << 20, size=count, dtype=np.int64).view(np.uint64)
+    X, Y = oracle.share(xs, n, 11, oracle.STREAM_X), oracle.share(ys, n, 11, oracle.STREAM_Y)
+    a, b, c = oracle.dealer_mul(n, count, seed=12)
+    r, rt, rm = oracle.trunc_dealer(n, count, f, seed=13)
+    Xd = spin.share(dev(xs), n, 11, oracle.STREAM_X)
+    assert (host(Xd) == X).all()
+    assert (host(spin.open(Xd, dev(a))) == oracle.open_(X, a)).all()
+    zo = oracle.beaver_mul(X, Y, a, b, c)
+    zd = spin.beaver_mul(Xd, dev(Y), dev(a), dev(b), dev(c))
+    assert (host(zd) == zo).all()
+    to = oracle.trunc(zo, r, rt, rm, f)
+    spin.trunc(zd, dev(r), dev(rt), dev(rm), f, out=zd)
+    assert (host(zd) == to).all()
+    want = oracle.trunc(oracle.lincomb([X, zo], [3, -5], 77), r, rt, rm, f)
+    got = spin.lincomb_trunc([Xd, dev(zo)], [3, -5], 77, f, (dev(r), dev(rt), dev(rm)))
+    assert (host(got) == want).all()
+
+
 # ----------------------------------------------------------------------------- Beaver matmul
 def matmul_case(n, batch, M, N, K, seed, path, X=None, Y=None, consistent=True):
     rng = np.random.default_rng(seed)
