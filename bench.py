@@ -34,9 +34,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--path", default="limb", choices=["limb", "valu"])
-    ap.add_argument("--workload", default="matmul", choices=["matmul", "poly", "matmul128"],
+    ap.add_argument("--workload", default="matmul", choices=["matmul", "poly", "matmul128", "matmul32"],
                     help="matmul: the Beaver-matmul hot path (the benchmark); poly: completed-square polynomial "
-                         "evaluation (Section 7.2 Eq. (4)) on the configuration's vector length")
+                         "evaluation (Section 7.2 Eq. (4)) on the configuration's vector length; matmul128 / matmul32: the "
+                         "Beaver matmul over the other two ring widths")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
@@ -151,16 +152,20 @@ def bench_poly(args):
                       "max_abs_error_vs_2^z": err, "stream_kernels": kernels}))
 
 
-def bench_matmul128(args):
-    """Side workload: the Beaver matmul over Z_2^128 (16 digits, 136 digit pairs per ring MAC), 2048^3, 2 parties."""
+def bench_matmul_other_ring(args, bits):
+    """Side workloads: the Beaver matmul over Z_2^128 (16 digits, 136 digit pairs per ring MAC; 2 parties,
+    2048^3) and over Z_2^32 (4 digits, 10 digit pairs; 2 parties, 8192^3)."""
     import torch
     from paper_2402_02320_amd import spin
-    R = spin.ring128
-    n, M = 2, 2048
+    R = spin.ring128 if bits == 128 else spin.ring32
+    n, M = (2, 2048) if bits == 128 else (2, 8192)
+    pairs = 136 if bits == 128 else 10
     path = spin.LIMB_MFMA if args.path == "limb" else spin.VALU
 
     def rnd(shape):
-        return torch.empty(shape + (2,), dtype=torch.int64, device="cuda").random_(-2 ** 62, 2 ** 62)
+        if bits == 128:
+            return torch.empty(shape + (2,), dtype=torch.int64, device="cuda").random_(-2 ** 62, 2 ** 62)
+        return torch.empty(shape, dtype=torch.int32, device="cuda").random_(-2 ** 31, 2 ** 31)
     X, Y, A, B, C = (rnd((n, 1, M, M)) for _ in range(5))
     Z = torch.empty_like(C)
     ws = torch.empty(R.beaver_matmul_workspace_bytes(n, 1, M, M, M, path), dtype=torch.uint8, device="cuda")
@@ -183,14 +188,17 @@ def bench_matmul128(args):
     gemm_ms = tot / cnt
     roof = None
     if path == spin.LIMB_MFMA:
-        ach = macs * 272 / (cnt / args.steps) / (gemm_ms * 1e-3) / 1e12      # 136 digit pairs x 2 ops
-        roof = {"bound": "mfma", "kernel": "limb128_gemm_kernel", "achieved": ach, "peak": PEAK_INT8_TOPS,
-                "unit": "TOP/s", "frac": ach / PEAK_INT8_TOPS, "traffic": None, "avg_launch_ms": gemm_ms}
-    print(json.dumps({"metric": "Z_2^128 ring MACs/s for Beaver matmul (side workload)", "value": macs / (ms * 1e-3),
-                      "unit": "ring MAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
-                      "higher_is_better": True, "vs_baseline": None, "dtype": "u128 (int8 digits, int32 accumulate)"
-                      if path == spin.LIMB_MFMA else "u128", "data": "synthetic",
-                      "config": {"workload": "2 parties, M=N=K=2048 over Z_2^128", "gemm_path": args.path},
+        ach = macs * 2 * pairs / (cnt / args.steps) / (gemm_ms * 1e-3) / 1e12      # digit pairs x (multiply + add)
+        roof = {"bound": "mfma", "kernel": "limb128_gemm_kernel" if bits == 128 else "limb_gemm_kernel<unsigned int>",
+                "achieved": ach, "peak": PEAK_INT8_TOPS, "unit": "TOP/s", "frac": ach / PEAK_INT8_TOPS,
+                "traffic": None, "avg_launch_ms": gemm_ms}
+    ring = "u%d" % bits
+    print(json.dumps({"metric": "Z_2^%d ring MACs/s for Beaver matmul (side workload)" % bits,
+                      "value": macs / (ms * 1e-3), "unit": "ring MAC/s", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "vs_baseline": None,
+                      "dtype": ring + " (int8 digits, int32 accumulate)" if path == spin.LIMB_MFMA else ring,
+                      "data": "synthetic",
+                      "config": {"workload": "%d parties, M=N=K=%d over Z_2^%d" % (n, M, bits), "gemm_path": args.path},
                       "roofline": roof, "gemm_avg_ms": gemm_ms, "pack_avg_ms": pk / pc if pc else None}))
 
 
@@ -211,8 +219,8 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "poly":
         return bench_poly(args)
-    if args.workload == "matmul128":
-        return bench_matmul128(args)
+    if args.workload in ("matmul128", "matmul32"):
+        return bench_matmul_other_ring(args, 128 if args.workload == "matmul128" else 32)
     c = workloads.CONFIGS[args.config]
     g = c.gemms[0]
     n, f = c.n, c.f

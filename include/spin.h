@@ -177,6 +177,37 @@ spin_status spin128_trunc(int n, size_t count, int f, const uint64_t *x,
                           const uint64_t *r, const uint64_t *r_top, const uint64_t *r_msb,
                           uint64_t *out, spin_stream stream);
 
+/* The same calls over the ring Z_2^32, the Fixed32 representation of Section 7.1 (mixing bit
+ * lengths): steps that do not need 64 bits run on 32-bit shares at half the bytes.  Ring elements
+ * are uint32_t, tensors party-major as before.  A 32-bit generator word is the low half of
+ * rand64 at the same index.  spin32_trunc: Truncate(x,f) = UnsignedTruncate(x + 2^30, 32, f) -
+ * 2^(30-f), tuple fields r_top = bits f..30 and r_msb = bit 31 of r, 1 <= f <= 29.  The limb
+ * path of spin32_beaver_matmul uses four digits (10 digit pairs) and never splits the inner
+ * dimension.  Everything else as documented at the 64-bit call.
+ *
+ * spin_cast_64_to_32 is the local Fixed64 -> Fixed32 cast of Section 7.1: out[k] = low 32 bits
+ * of in[k], applied by every party to its own share (pass all n*count share words at once);
+ * the opened value is preserved while it lies in [-2^31, 2^31).  in: [count] uint64_t,
+ * out: [count] uint32_t, must not overlap.                                                      */
+spin_status spin32_share(const uint32_t *x, size_t count, int n, uint64_t seed, uint64_t stream_id,
+                         uint32_t *shares, spin_stream stream);
+spin_status spin32_open(const uint32_t *shares, const uint32_t *mask, size_t count, int n,
+                        uint32_t *out, spin_stream stream);
+spin_status spin32_beaver_matmul(int n, int batch, int M, int N, int K,
+                                 const uint32_t *X, const uint32_t *Y,
+                                 const uint32_t *A, const uint32_t *B, const uint32_t *C,
+                                 uint32_t *Z, spin_gemm_path path,
+                                 void *workspace, size_t workspace_bytes, spin_stream stream);
+size_t spin32_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path);
+spin_status spin32_beaver_mul(int n, size_t count,
+                              const uint32_t *x, const uint32_t *y,
+                              const uint32_t *a, const uint32_t *b, const uint32_t *c,
+                              uint32_t *z, spin_stream stream);
+spin_status spin32_trunc(int n, size_t count, int f, const uint32_t *x,
+                         const uint32_t *r, const uint32_t *r_top, const uint32_t *r_msb,
+                         uint32_t *out, spin_stream stream);
+spin_status spin_cast_64_to_32(const uint64_t *in, size_t count, uint32_t *out, spin_stream stream);
+
 /* Per-kernel timing for benchmarks (measurement aid, not part of the protocol).
  * While enabled, every kernel the library launches is bracketed by a pair of
  * HIP events recorded on the caller's stream; events are created on demand
@@ -195,7 +226,8 @@ typedef enum {
     SPIN_KERNEL_GEMM_VALU = 7,
     SPIN_KERNEL_LINCOMB = 8,
     SPIN_KERNEL_BINARY = 9,     /* bshare, bopen, beaver_and */
-    SPIN_KERNEL_COUNT = 10
+    SPIN_KERNEL_CAST = 10,      /* spin_cast_64_to_32 */
+    SPIN_KERNEL_COUNT = 11
 } spin_kernel;
 void spin_profile_enable(int on);
 spin_status spin_profile_read(spin_kernel kernel, double *total_ms, unsigned *launches);

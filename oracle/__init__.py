@@ -231,6 +231,13 @@ def local_shift_trunc(x, f):
     return out
 
 
+def cast_64_to_32(shares):
+    """Section 7.1 (mixing bit lengths): the local Fixed64 -> Fixed32 cast.  Every party reduces its
+    own share mod 2^32; the result is returned as ring-32 elements in uint64 storage, the form the
+    l = 32 calls of this module take."""
+    return _u64(shares) & np.uint64(0xFFFFFFFF)
+
+
 def absorb(h, v):
     return int(lib().oracle_absorb(h, v))
 

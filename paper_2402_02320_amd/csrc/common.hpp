@@ -13,7 +13,10 @@
 namespace spin {
 
 typedef uint64_t u64;
+typedef uint32_t u32;             // ring Z_2^32 (the Fixed32 representation of Section 7.1)
 typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+typedef u32 u32x2 __attribute__((ext_vector_type(2)));
+typedef u32 u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned __int128 u128;   // ring Z_2^128: 16 bytes, little-endian (low word first)
 
 // ---- counter generator (specified in include/spin.h at spin_random) --------
@@ -64,7 +67,7 @@ struct KernelTimer {
 // ---- internal launchers (defined in the .hip files) -------------------------
 spin_status launch_random(u64 *out, size_t count, u64 key, u64 first_idx, hipStream_t s);
 spin_status launch_share(const u64 *x, size_t count, int n, const PartyKeys &keys, u64 *shares, hipStream_t s);
-// T = u64 or u128 (instantiated in elementwise.hip)
+// T = u32, u64 or u128 (instantiated in elementwise.hip)
 template <class T> spin_status launch_open(const T *shares, const T *mask, size_t count, int n, T *out, hipStream_t s);
 template <class T>
 spin_status launch_beaver_mul(int n, size_t count, const T *x, const T *y, const T *a, const T *b, const T *c, T *z,
@@ -72,6 +75,8 @@ spin_status launch_beaver_mul(int n, size_t count, const T *x, const T *y, const
 template <class T>
 spin_status launch_trunc(int n, size_t count, int f, const T *x, const T *r, const T *r_top, const T *r_msb, T *out,
                          hipStream_t s);
+spin_status launch_share32(const u32 *x, size_t count, int n, const PartyKeys &keys, u32 *shares, hipStream_t s);
+spin_status launch_cast_low(const u64 *in, size_t count, u32 *out, hipStream_t s);
 spin_status launch_share128(const u128 *x, size_t count, int n, const PartyKeys &keys, u128 *shares, hipStream_t s);
 
 spin_status launch_bshare(const u64 *x, size_t count, int n, const PartyKeys &keys, u64 *shares, hipStream_t s);
@@ -90,11 +95,14 @@ template <class T> struct MatmulArgsT {
 };
 typedef MatmulArgsT<u64> MatmulArgs;
 typedef MatmulArgsT<u128> MatmulArgs128;
-// elem_bytes = 8 (Z_2^64) or 16 (Z_2^128)
+typedef MatmulArgsT<u32> MatmulArgs32;
+// elem_bytes = 4 (Z_2^32), 8 (Z_2^64) or 16 (Z_2^128)
 size_t valu_workspace_bytes(int n, int batch, int M, int N, int K, int elem_bytes);
 template <class T> spin_status launch_matmul_valu(const MatmulArgsT<T> &a, hipStream_t s);
 size_t limb_workspace_bytes(int n, int batch, int M, int N, int K);
 spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s);
+size_t limb32_workspace_bytes(int n, int batch, int M, int N, int K);
+spin_status launch_matmul_limb32(const MatmulArgs32 &a, hipStream_t s);
 size_t limb128_workspace_bytes(int n, int batch, int M, int N, int K);
 spin_status launch_matmul_limb128(const MatmulArgs128 &a, hipStream_t s);
 

@@ -10,6 +10,8 @@
 // lane: measured on MI355X at n = 5 and 2^24 elements, 8-byte lanes sustain
 // about 8 % more HBM bandwidth than 16-byte lanes for that access pattern
 // (5.6 against 5.2 TB/s for trunc).
+#include <initializer_list>
+
 #include "common.hpp"
 
 namespace spin {
@@ -33,18 +35,35 @@ template <bool NT, class V> __device__ inline void st(V *p, V v)
     else *p = v;
 }
 
-// V = u64x2 (two ring elements per lane) or u64 (odd counts, whose party rows
-// are only 8-byte aligned).
+// Lane types.  V = u64x2 (two ring elements per lane) or u64 (odd counts, whose party rows are only
+// 8-byte aligned); for the 4-byte ring u32x4 / u32x2 / u32 likewise.  `bits` is the ring width l.
 template <class V> struct Lanes;
 template <> struct Lanes<u64x2> { static constexpr int width = 2; };
-template <> struct Lanes<u64>   { static constexpr int width = 1; };
-template <> struct Lanes<u128>  { static constexpr int width = 1; };
+template <> struct Lanes<u64>   { static constexpr int width = 1, bits = 64; };
+template <> struct Lanes<u128>  { static constexpr int width = 1, bits = 128; };
+template <> struct Lanes<u32x4> { static constexpr int width = 4; };
+template <> struct Lanes<u32x2> { static constexpr int width = 2, bits = 32; };
+template <> struct Lanes<u32>   { static constexpr int width = 1, bits = 32; };
 
 template <class V> __device__ inline V gen(u64 key, u64 idx);
 template <> __device__ inline u64 gen<u64>(u64 key, u64 idx) { return absorb(key, idx); }
 template <> __device__ inline u64x2 gen<u64x2>(u64 key, u64 idx)
 {
     u64x2 v; v.x = absorb(key, idx); v.y = absorb(key, idx + 1); return v;
+}
+
+// a 32-bit generator word is the low half of the 64-bit output at the same index
+template <> __device__ inline u32 gen<u32>(u64 key, u64 idx) { return (u32)absorb(key, idx); }
+template <> __device__ inline u32x2 gen<u32x2>(u64 key, u64 idx)
+{
+    u32x2 v; v.x = (u32)absorb(key, idx); v.y = (u32)absorb(key, idx + 1); return v;
+}
+template <> __device__ inline u32x4 gen<u32x4>(u64 key, u64 idx)
+{
+    u32x4 v;
+    v.x = (u32)absorb(key, idx); v.y = (u32)absorb(key, idx + 1);
+    v.z = (u32)absorb(key, idx + 2); v.w = (u32)absorb(key, idx + 3);
+    return v;
 }
 
 // a 128-bit generator word is the pair of 64-bit outputs 2 idx (low) and 2 idx + 1 (high)
@@ -129,7 +148,7 @@ template <int NP, class T, bool NT>
 __device__ inline void truncate_and_store(const T (&y)[NP], const T *__restrict__ r, const T *__restrict__ r_top,
                                           const T *__restrict__ r_msb, size_t count, size_t v, int f, T *out)
 {
-    constexpr int L = 8 * sizeof(T);               // ring width l
+    constexpr int L = Lanes<T>::bits;              // ring width l
     T rt[NP], rm[NP];
     T c = (T)1 << (L - 2);
 #pragma unroll
@@ -189,6 +208,23 @@ __global__ __launch_bounds__(kBlock) void lincomb_trunc_kernel(LincombTerms t, u
 #pragma unroll
         for (int i = 0; i < NP; ++i) st<NT>(out + (size_t)i * count + v, y[i]);
     }
+}
+
+// Fixed64 -> Fixed32 (Section 7.1): every party keeps the low 32 bits of its own share; the sum of the
+// low halves is the value mod 2^32, which is the value itself while it fits 32 bits.
+template <class VI, class VO, bool NT>
+__global__ __launch_bounds__(kBlock) void cast_low_kernel(const VI *__restrict__ in, size_t nvec, VO *__restrict__ out)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= nvec) return;
+    st<NT>(out + v, __builtin_convertvector(ld<NT>(in + v), VO));
+}
+template <bool NT>
+__global__ __launch_bounds__(kBlock) void cast_low_kernel1(const u64 *__restrict__ in, size_t count, u32 *__restrict__ out)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= count) return;
+    st<NT>(out + v, (u32)ld<NT>(in + v));
 }
 
 // ---- binary sharing: the same three streams with XOR for + and AND for * (Section 4.1, 4.3) ----
@@ -258,6 +294,19 @@ template <class F> inline void for_streaming(size_t bytes, F &&fn)
     else fn(std::false_type());
 }
 
+// Calls fn(lane type tag, number of lane vectors).  The 4-byte ring moves two elements per lane when
+// the count is even (party rows then stay 8-byte aligned) and every pointer is 8-byte aligned; other
+// rings move one element per lane.
+template <class T, class F> inline void for_lane_type(size_t count, std::initializer_list<const void *> ptrs, F &&fn)
+{
+    if constexpr (std::is_same<T, u32>::value) {
+        bool pair = count % 2 == 0;
+        for (const void *p : ptrs) pair = pair && ((uintptr_t)p % 8 == 0);
+        if (pair) { fn((u32x2 *)nullptr, count / 2); return; }
+    }
+    fn((T *)nullptr, count);
+}
+
 }  // namespace
 
 spin_status launch_random(u64 *out, size_t count, u64 key, u64 first_idx, hipStream_t s)
@@ -294,8 +343,15 @@ spin_status launch_open(const T *shares, const T *mask, size_t count, int n, T *
         constexpr int NP = decltype(np)::value;
         for_streaming((size_t)n * count * sizeof(T), [&](auto nt) {
             constexpr bool NT = decltype(nt)::value;
-            if (mask) open_kernel<NP, true, T, NT><<<grid_for(count), kBlock, 0, s>>>(shares, mask, count, out);
-            else open_kernel<NP, false, T, NT><<<grid_for(count), kBlock, 0, s>>>(shares, nullptr, count, out);
+            for_lane_type<T>(count, {shares, mask, out}, [&](auto *tag, size_t nvec) {
+                using V = std::remove_pointer_t<decltype(tag)>;
+                if (mask)
+                    open_kernel<NP, true, V, NT><<<grid_for(nvec), kBlock, 0, s>>>((const V *)shares, (const V *)mask,
+                                                                                  nvec, (V *)out);
+                else
+                    open_kernel<NP, false, V, NT><<<grid_for(nvec), kBlock, 0, s>>>((const V *)shares, nullptr, nvec,
+                                                                                   (V *)out);
+            });
         });
     });
     return check_launch("spin_open");
@@ -308,8 +364,11 @@ spin_status launch_beaver_mul(int n, size_t count, const T *x, const T *y, const
     KernelTimer timer(SPIN_KERNEL_BEAVER_MUL, s);
     for_party_count(n, [&](auto np) {
         for_streaming((size_t)n * count * sizeof(T), [&](auto nt) {
-            beaver_mul_kernel<decltype(np)::value, T, decltype(nt)::value><<<grid_for(count), kBlock, 0, s>>>(
-                x, y, a, b, c, count, z);
+            for_lane_type<T>(count, {x, y, a, b, c, z}, [&](auto *tag, size_t nvec) {
+                using V = std::remove_pointer_t<decltype(tag)>;
+                beaver_mul_kernel<decltype(np)::value, V, decltype(nt)::value><<<grid_for(nvec), kBlock, 0, s>>>(
+                    (const V *)x, (const V *)y, (const V *)a, (const V *)b, (const V *)c, nvec, (V *)z);
+            });
         });
     });
     return check_launch("spin_beaver_mul");
@@ -322,8 +381,11 @@ spin_status launch_trunc(int n, size_t count, int f, const T *x, const T *r, con
     KernelTimer timer(SPIN_KERNEL_TRUNC, s);
     for_party_count(n, [&](auto np) {
         for_streaming((size_t)n * count * sizeof(T), [&](auto nt) {
-            trunc_kernel<decltype(np)::value, T, decltype(nt)::value><<<grid_for(count), kBlock, 0, s>>>(
-                x, r, r_top, r_msb, count, f, out);
+            for_lane_type<T>(count, {x, r, r_top, r_msb, out}, [&](auto *tag, size_t nvec) {
+                using V = std::remove_pointer_t<decltype(tag)>;
+                trunc_kernel<decltype(np)::value, V, decltype(nt)::value><<<grid_for(nvec), kBlock, 0, s>>>(
+                    (const V *)x, (const V *)r, (const V *)r_top, (const V *)r_msb, nvec, f, (V *)out);
+            });
         });
     });
     return check_launch("spin_trunc");
@@ -338,6 +400,42 @@ spin_status launch_share128(const u128 *x, size_t count, int n, const PartyKeys 
     return check_launch("spin128_share");
 }
 
+spin_status launch_share32(const u32 *x, size_t count, int n, const PartyKeys &keys, u32 *shares, hipStream_t s)
+{
+    KernelTimer timer(SPIN_KERNEL_SHARE, s);
+    for_party_count(n, [&](auto np) {
+        constexpr int NP = decltype(np)::value;
+        if (count % 4 == 0)
+            share_kernel<NP, u32x4, false><<<grid_for(count / 4), kBlock, 0, s>>>((const u32x4 *)x, count / 4, keys,
+                                                                                 (u32x4 *)shares);
+        else if (count % 2 == 0)
+            share_kernel<NP, u32x2, false><<<grid_for(count / 2), kBlock, 0, s>>>((const u32x2 *)x, count / 2, keys,
+                                                                                 (u32x2 *)shares);
+        else
+            share_kernel<NP, u32, false><<<grid_for(count), kBlock, 0, s>>>(x, count, keys, shares);
+    });
+    return check_launch("spin32_share");
+}
+
+spin_status launch_cast_low(const u64 *in, size_t count, u32 *out, hipStream_t s)
+{
+    KernelTimer timer(SPIN_KERNEL_CAST, s);
+    for_streaming(count * sizeof(u64), [&](auto nt) {
+        constexpr bool NT = decltype(nt)::value;
+        if (count % 2 == 0)
+            cast_low_kernel<u64x2, u32x2, NT><<<grid_for(count / 2), kBlock, 0, s>>>((const u64x2 *)in, count / 2,
+                                                                                    (u32x2 *)out);
+        else
+            cast_low_kernel1<NT><<<grid_for(count), kBlock, 0, s>>>(in, count, out);
+    });
+    return check_launch("spin_cast_64_to_32");
+}
+
+template spin_status launch_open<u32>(const u32 *, const u32 *, size_t, int, u32 *, hipStream_t);
+template spin_status launch_beaver_mul<u32>(int, size_t, const u32 *, const u32 *, const u32 *, const u32 *, const u32 *,
+                                            u32 *, hipStream_t);
+template spin_status launch_trunc<u32>(int, size_t, int, const u32 *, const u32 *, const u32 *, const u32 *, u32 *,
+                                       hipStream_t);
 template spin_status launch_open<u64>(const u64 *, const u64 *, size_t, int, u64 *, hipStream_t);
 template spin_status launch_open<u128>(const u128 *, const u128 *, size_t, int, u128 *, hipStream_t);
 template spin_status launch_beaver_mul<u64>(int, size_t, const u64 *, const u64 *, const u64 *, const u64 *, const u64 *,

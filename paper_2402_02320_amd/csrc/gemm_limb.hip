@@ -1,6 +1,6 @@
-// Exact ring GEMM over Z_2^64 on the int8 matrix cores.
+// Exact ring GEMM over Z_2^64 (and, with four digits, Z_2^32) on the int8 matrix cores.
 //
-// Every uint64 a is rewritten as eight balanced digits s_0..s_7 in [-128,127]
+// Z_2^64: every uint64 a is rewritten as eight balanced digits s_0..s_7 in [-128,127]
 // with  sum_i s_i 256^i == a  (mod 2^64)   [t = a + 0x80..80; s = t ^ 0x80..80].
 // Then  a*b == sum_{i+j<=7} s_i t_j 256^(i+j)  (mod 2^64): the 28 digit pairs
 // with i+j >= 8 are multiples of 2^64.  The 36 surviving pairs are int8 x int8
@@ -11,7 +11,11 @@
 // d <= 3 must not overflow: (d+1) * Ktot * 2^14 < 2^31  <=>  Ktot < 2^15.
 // For d >= 4 only the low 32 bits matter and the accumulators wrap (two's
 // complement), which leaves those bits right.  The host splits the inner
-// dimension into chunks of at most kMaxChunkTiles k-tiles per operand pair.
+// dimension into chunks of at most 511 k-tiles per operand pair.
+//
+// Z_2^32 (the Fixed32 representation of Section 7.1): four digits, the 10 pairs with i+j <= 3, four
+// diagonals; every diagonal needs at most 32 exact bits, so wrapping accumulators are always right
+// and the inner dimension is never split.
 //
 // Kernels:
 //  pack_left/right_kernel (limb_common.hpp)  open E (or F), convert E/A_i (or F/B_i') to
@@ -21,9 +25,9 @@
 //                32x32x32 step into 8 diagonal accumulators, recombined once.
 #include "limb_common.hpp"
 
-// Interleave of one k-step of the GEMM (slots = MFMA index within the step, 72 per step for the 64x32
-// wave tile): an LDS read after every RD_EVERY-th MFMA from slot 0, a direct-to-LDS load after every
-// LD_EVERY-th MFMA from slot LD_FIRST.
+// Interleave of one k-step of the 64-bit GEMM (slots = MFMA index within the step, 72 per step for the
+// 64x32 wave tile): an LDS read after every RD_EVERY-th MFMA from slot 0, a direct-to-LDS load after
+// every LD_EVERY-th MFMA from slot LD_FIRST.
 #ifndef SPIN_TUNE_RD_EVERY
 #define SPIN_TUNE_RD_EVERY 2
 #endif
@@ -37,44 +41,60 @@
 namespace spin {
 namespace {
 
-constexpr int kDigits = 8;
-constexpr int kMaxChunkTiles = 511;  // 2*511*32 = 32704 < 2^15 digit products per accumulator
+// Per ring: digits, workgroup shape (waves are 2 x 2, each WM x WN MFMA tiles of 32 x 32; ND * WM * WN
+// * 16 accumulator registers <= 256), longest run of k-tiles one launch may accumulate, and the slots
+// of the interleave.
+template <class T> struct Ring;
+template <> struct Ring<u64> {
+    static constexpr int WM = 2, WN = 1;
+    static constexpr int max_chunk_tiles = 511;        // 2*511*32 = 32704 < 2^15 digit products per accumulator
+    static constexpr int rd_every = SPIN_TUNE_RD_EVERY, ld_first = SPIN_TUNE_LD_FIRST, ld_every = SPIN_TUNE_LD_EVERY;
+};
+template <> struct Ring<u32> {
+    static constexpr int WM = 2, WN = 2;
+    static constexpr int max_chunk_tiles = 1 << 20;    // no headroom limit; keeps the step count an int
+    static constexpr int rd_every = 2, ld_first = 5, ld_every = 4;   // 40 MFMAs, 16 reads, 8 loads per step
+};
 
 // ------------------------------------------------------------------ GEMM ---
-struct GemmArgs {
-    const char *packA;   // [n+1][batch][nblkA][KT][8][1024]: slot 0 = E, slot 1+i = A_i
-    const char *packB;   // [n+1][batch][nblkB][KT][8][1024]: slot 0 = F, slot 1+i = B_i'
-    const u64 *C;        // [n][batch][M][N]  (or Z itself for the later k-chunks)
-    u64 *Z;
+template <class T> struct GemmArgs {
+    const char *packA;   // [n+1][batch][nblkA][KT][ND][1024]: slot 0 = E, slot 1+i = A_i
+    const char *packB;   // [n+1][batch][nblkB][KT][ND][1024]: slot 0 = F, slot 1+i = B_i'
+    const T *C;          // [n][batch][M][N]  (or Z itself for the later k-chunks)
+    T *Z;
     int n, batch, M, N;
     int nblkA, nblkB, KT;
     int kt0, ktn;        // this launch covers k-tiles [kt0, kt0+ktn) of both operand pairs
     int tilesM, tilesN;
 };
 
-template <int WM, int WN>
+template <class T>
 struct GemmShape {
+    static constexpr int ND = sizeof(T);                         // digits per ring element
+    static constexpr int WM = Ring<T>::WM, WN = Ring<T>::WN;
     static constexpr int NSTAGE = 3;                             // LDS ring: one stage read, two in flight
     static constexpr int BM = 2 * 32 * WM, BN = 2 * 32 * WN;     // 4 waves as 2 x 2
-    static constexpr int FA = BM / 32 * kDigits, FB = BN / 32 * kDigits;
+    static constexpr int FA = BM / 32 * ND, FB = BN / 32 * ND;
     static constexpr int stage_bytes = (FA + FB) * kFrag;
     static constexpr int lds_bytes = NSTAGE * stage_bytes;
     static constexpr int loads_per_wave = (FA + FB) / 4;
-    static constexpr int frags_per_wave = (WM + WN) * kDigits;   // LDS -> register reads per step
-    static constexpr int mfma_per_step = 36 * WM * WN;
+    static constexpr int frags_per_wave = (WM + WN) * ND;        // LDS -> register reads per step
+    static constexpr int mfma_per_step = ND * (ND + 1) / 2 * WM * WN;
+    static_assert(ND * WM * WN * 16 <= 256, "accumulators exceed the AGPR file");
 };
 
-// Pipeline (per wave; step s covers one 32-deep k-tile of one operand pair):
+// Pipeline (per wave; step s covers one 32-deep k-tile of one operand pair; counts for Z_2^64):
 //   G(s)  12 direct-to-LDS loads of this wave's share of step s into LDS stage s % 3
 //   R(s)  24 ds_read_b128 of the wave's fragments of step s into registers
 //   M(s)  72 MFMAs of step s
 // Iteration s: [wait G(s+1); barrier]  then M(s) interleaved with R(s+1) and G(s+3).
 // The barrier at the top of iteration s also tells every wave that all R(s) are done, so stage s % 3
 // can be refilled by G(s+3).  Two groups of loads are in flight while a step computes.
-template <int WM, int WN>
-__global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
+template <class T>
+__global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
 {
-    using S = GemmShape<WM, WN>;
+    using S = GemmShape<T>;
+    constexpr int kDigits = S::ND, WM = S::WM, WN = S::WN;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
 
     const int lane = threadIdx.x % 64;
@@ -100,8 +120,8 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
     // Load cursor: where the loads of the next step to be fetched come from and go to.  It lives on
     // the scalar unit and advances by one k-tile per step (no division, no per-load selects); at the
     // switch from the first operand pair to the second it jumps to the other fragment streams.
-    // This wave loads fragments f = 4q + wave, q < loads_per_wave: row/column block f / 8 = q / 2 of
-    // the tile and digit f % 8 = 4 (q % 2) + wave, so only q-dependent constants remain per load.
+    // This wave loads fragments f = 4q + wave, q < loads_per_wave: row/column block f / ND = q / (ND/4)
+    // of the tile and digit f % ND = 4 (q % (ND/4)) + wave, so only q-dependent constants remain per load.
     const size_t blk_stride = (size_t)g.KT * (kDigits * kFrag);
     const size_t kt0_off = (size_t)g.kt0 * (kDigits * kFrag) + wave * kFrag;
     const char *ld_a = a_first + (size_t)tm * (S::BM / 32) * blk_stride + kt0_off;
@@ -113,8 +133,9 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
     const u32 lds_wrap = lds0 + wave * kFrag + (S::NSTAGE - 1) * S::stage_bytes;
     auto issue_load = [&](int q) {                       // q is a compile-time constant after unrolling
         constexpr int qa = S::FA / 4;                    // loads of left-operand fragments per wave
-        const char *p = q < qa ? ld_a + (size_t)(q / 2) * blk_stride + (q % 2) * (4 * kFrag)
-                               : ld_b + (size_t)((q - qa) / 2) * blk_stride + ((q - qa) % 2) * (4 * kFrag);
+        constexpr int per_blk = kDigits / 4;             // loads of this wave per 32-row (32-column) block
+        const char *p = q < qa ? ld_a + (size_t)(q / per_blk) * blk_stride + (q % per_blk) * (4 * kFrag)
+                               : ld_b + (size_t)((q - qa) / per_blk) * blk_stride + ((q - qa) % per_blk) * (4 * kFrag);
         load_fragment_to_lds(p, ld_lds + q * (4 * kFrag), lane16);
     };
     auto advance_load_cursor = [&]() {
@@ -196,10 +217,10 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
                         // scalar work between them.  sched_barrier pins this order: left alone, the
                         // scheduler sinks each read next to its first use and the MFMA pipe then waits
                         // out the LDS latency.
-                        constexpr int rd_every = SPIN_TUNE_RD_EVERY;
+                        constexpr int rd_every = Ring<T>::rd_every;
                         constexpr int rd_last = rd_every * (S::frags_per_wave - 1);
-                        constexpr int ld_first = SPIN_TUNE_LD_FIRST;
-                        constexpr int ld_every = SPIN_TUNE_LD_EVERY;
+                        constexpr int ld_first = Ring<T>::ld_first;
+                        constexpr int ld_every = Ring<T>::ld_every;
                         constexpr int ld_last = ld_first + ld_every * (S::loads_per_wave - 1);
                         static_assert(rd_every >= 1 && ld_every >= 1 && ld_last + 1 < S::mfma_per_step &&
                                       rd_last + 1 < S::mfma_per_step, "tile too small for this interleave");
@@ -222,26 +243,26 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
                         ++slot;
                     }
     };
-    using T = std::true_type;
+    using Y = std::true_type;
     using F = std::false_type;
     using B0 = std::integral_constant<int, 0>;
     using B1 = std::integral_constant<int, 1>;
     int s = 0;
     for (; s + 4 < steps; s += 2) {                       // steps is even; both halves have all neighbours
-        iteration(B0(), T(), T(), T());
-        iteration(B1(), T(), T(), T());
+        iteration(B0(), Y(), Y(), Y());
+        iteration(B1(), Y(), Y(), Y());
     }
     if (steps >= 4) {
-        iteration(B0(), T(), T(), T());                   // step steps-4: loads the last step
-        iteration(B1(), F(), T(), T());
+        iteration(B0(), Y(), Y(), Y());                   // step steps-4: loads the last step
+        iteration(B1(), F(), Y(), Y());
     }
-    iteration(B0(), F(), T(), F());                       // step steps-2
+    iteration(B0(), F(), Y(), F());                       // step steps-2
     iteration(B1(), F(), F(), F());                       // step steps-1
 
     // recombine the diagonals and add C_i
     const size_t mat = (size_t)g.M * g.N;
-    const u64 *Cm = g.C + (size_t)pb * mat;
-    u64 *Zm = g.Z + (size_t)pb * mat;
+    const T *Cm = g.C + (size_t)pb * mat;
+    T *Zm = g.Z + (size_t)pb * mat;
 #pragma unroll
     for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -251,72 +272,87 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs g)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = row0 + 8 * (r / 4) + r % 4;
-                u64 v = 0;
+                T v = 0;
 #pragma unroll
-                for (int d = 0; d < kDigits; ++d) v += (u64)(int64_t)acc[i][j][d][r] << (8 * d);
+                for (int d = 0; d < kDigits; ++d) v += (T)(int64_t)acc[i][j][d][r] << (8 * d);
                 if (row < g.M && col < g.N) Zm[(size_t)row * g.N + col] = Cm[(size_t)row * g.N + col] + v;
             }
         }
 }
 
 // ------------------------------------------------------------------ host ---
-constexpr int kWM = 2, kWN = 1;
-using Shape = GemmShape<kWM, kWN>;
-
-
 struct Plan {
     int KT, nblkA, nblkB, tilesM, tilesN;
     size_t packA_bytes, packB_bytes;
 };
-inline Plan make_plan(int n, int batch, int M, int N, int K)
+template <class T> inline Plan make_plan(int n, int batch, int M, int N, int K)
 {
+    using S = GemmShape<T>;
     Plan p;
     p.KT = ceil_div(K, 32);
-    p.tilesM = ceil_div(M, Shape::BM);
-    p.tilesN = ceil_div(N, Shape::BN);
-    p.nblkA = p.tilesM * (Shape::BM / 32);
-    p.nblkB = p.tilesN * (Shape::BN / 32);
-    p.packA_bytes = (size_t)(n + 1) * batch * p.nblkA * p.KT * (kDigits * kFrag);
-    p.packB_bytes = (size_t)(n + 1) * batch * p.nblkB * p.KT * (kDigits * kFrag);
+    p.tilesM = ceil_div(M, S::BM);
+    p.tilesN = ceil_div(N, S::BN);
+    p.nblkA = p.tilesM * (S::BM / 32);
+    p.nblkB = p.tilesN * (S::BN / 32);
+    p.packA_bytes = (size_t)(n + 1) * batch * p.nblkA * p.KT * (S::ND * kFrag);
+    p.packB_bytes = (size_t)(n + 1) * batch * p.nblkB * p.KT * (S::ND * kFrag);
     return p;
+}
+
+template <class T> spin_status launch_limb(const MatmulArgsT<T> &a, hipStream_t s, const char *where_pack, const char *where_gemm)
+{
+    using S = GemmShape<T>;
+    const Plan p = make_plan<T>(a.n, a.batch, a.M, a.N, a.K);
+    char *packA = (char *)a.workspace;
+    char *packB = packA + p.packA_bytes;
+
+    launch_pack<T>(a, packA, packB, p.nblkA, p.nblkB, p.KT, s);
+    spin_status st = check_launch(where_pack);
+    if (st != SPIN_OK) return st;
+
+    static bool attr_set = false;                        // one flag per ring type
+    auto kernel = limb_gemm_kernel<T>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           S::lds_bytes);
+        if (e != hipSuccess) { note_hip_error(e, "hipFuncSetAttribute"); return SPIN_EHIP; }
+        attr_set = true;
+    }
+    GemmArgs<T> g{packA, packB, a.C, a.Z, a.n, a.batch, a.M, a.N, p.nblkA, p.nblkB, p.KT, 0, 0, p.tilesM, p.tilesN};
+    const long total = (long)p.tilesM * p.tilesN * a.n * a.batch;
+    constexpr int chunk = Ring<T>::max_chunk_tiles;
+    for (int kt0 = 0; kt0 < p.KT; kt0 += chunk) {
+        g.kt0 = kt0;
+        g.ktn = p.KT - kt0 < chunk ? p.KT - kt0 : chunk;
+        g.C = kt0 == 0 ? a.C : a.Z;                      // later chunks accumulate onto Z
+        KernelTimer timer(SPIN_KERNEL_GEMM_LIMB, s);
+        kernel<<<(unsigned)total, 256, S::lds_bytes, s>>>(g);
+    }
+    return check_launch(where_gemm);
 }
 
 }  // namespace
 
 size_t limb_workspace_bytes(int n, int batch, int M, int N, int K)
 {
-    Plan p = make_plan(n, batch, M, N, K);
+    Plan p = make_plan<u64>(n, batch, M, N, K);
+    return p.packA_bytes + p.packB_bytes;
+}
+
+size_t limb32_workspace_bytes(int n, int batch, int M, int N, int K)
+{
+    Plan p = make_plan<u32>(n, batch, M, N, K);
     return p.packA_bytes + p.packB_bytes;
 }
 
 spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s)
 {
-    const Plan p = make_plan(a.n, a.batch, a.M, a.N, a.K);
-    char *packA = (char *)a.workspace;
-    char *packB = packA + p.packA_bytes;
+    return launch_limb<u64>(a, s, "spin_beaver_matmul(pack)", "spin_beaver_matmul(limb gemm)");
+}
 
-    launch_pack<u64>(a, packA, packB, p.nblkA, p.nblkB, p.KT, s);
-    spin_status st = check_launch("spin_beaver_matmul(pack)");
-    if (st != SPIN_OK) return st;
-
-    static bool attr_set = false;
-    auto kernel = limb_gemm_kernel<kWM, kWN>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           Shape::lds_bytes);
-        if (e != hipSuccess) { note_hip_error(e, "hipFuncSetAttribute"); return SPIN_EHIP; }
-        attr_set = true;
-    }
-    GemmArgs g{packA, packB, a.C, a.Z, a.n, a.batch, a.M, a.N, p.nblkA, p.nblkB, p.KT, 0, 0, p.tilesM, p.tilesN};
-    const long total = (long)p.tilesM * p.tilesN * a.n * a.batch;
-    for (int kt0 = 0; kt0 < p.KT; kt0 += kMaxChunkTiles) {
-        g.kt0 = kt0;
-        g.ktn = p.KT - kt0 < kMaxChunkTiles ? p.KT - kt0 : kMaxChunkTiles;
-        g.C = kt0 == 0 ? a.C : a.Z;                      // later chunks accumulate onto Z
-        KernelTimer timer(SPIN_KERNEL_GEMM_LIMB, s);
-        kernel<<<(unsigned)total, 256, Shape::lds_bytes, s>>>(g);
-    }
-    return check_launch("spin_beaver_matmul(limb gemm)");
+spin_status launch_matmul_limb32(const MatmulArgs32 &a, hipStream_t s)
+{
+    return launch_limb<u32>(a, s, "spin32_beaver_matmul(pack)", "spin32_beaver_matmul(limb gemm)");
 }
 
 }  // namespace spin

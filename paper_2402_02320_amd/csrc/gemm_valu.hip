@@ -1,5 +1,5 @@
 // Baseline ring GEMM on the vector ALU: Z_i = C_i + E.B_i' + A_i.F with native
-// 64-bit (or, for Z_2^128, __int128) multiply-add, LDS-tiled (Section 6.1's design point -- native int64
+// 64-bit (for Z_2^32 32-bit, for Z_2^128 __int128) multiply-add, LDS-tiled (Section 6.1's design point -- native int64
 // arithmetic staged through shared memory -- kept as the reference path the
 // limb-MFMA path is measured against).  B_0' = B_0 + F folds party 0's public
 // E.F term into its first product.
@@ -107,6 +107,7 @@ template <class T> spin_status launch_matmul_valu(const MatmulArgsT<T> &a, hipSt
     valu_gemm_kernel<T><<<grid, 256, 0, s>>>(a.n, a.batch, a.M, a.N, a.K, E, F, a.A, a.B, a.C, a.Z);
     return check_launch("spin_beaver_matmul(valu)");
 }
+template spin_status launch_matmul_valu<u32>(const MatmulArgsT<u32> &, hipStream_t);
 template spin_status launch_matmul_valu<u64>(const MatmulArgsT<u64> &, hipStream_t);
 template spin_status launch_matmul_valu<u128>(const MatmulArgsT<u128> &, hipStream_t);
 

@@ -1,8 +1,8 @@
-// What the limb-decomposed GEMMs over Z_2^64 and Z_2^128 share: the balanced-digit conversion, the
+// What the limb-decomposed GEMMs over Z_2^32, Z_2^64 and Z_2^128 share: the balanced-digit conversion, the
 // fragment layout and the two pack kernels that open E (F) and lay all left (right) operands out as
 // int8 MFMA fragments, the direct-to-LDS load, and the mapping of workgroup ids to output tiles.
 //
-// A ring element of ND bytes (ND = 8 or 16) is rewritten as ND balanced digits s_i in [-128,127] with
+// A ring element of ND bytes (ND = 4, 8 or 16) is rewritten as ND balanced digits s_i in [-128,127] with
 // sum_i s_i 256^i == a (mod 2^(8 ND)):  t = a + 0x80..80;  s = t ^ 0x80..80 (bytes read as int8).
 // Fragment store: [slot][batch][blk][kt][digit][1024 B]; in one 1 KiB fragment lane l's 16 bytes at
 // offset 16 l are digit d of elements (row or column 32 blk + l % 32, k = 32 kt + 16 (l / 32) + 0..15),
@@ -15,11 +15,11 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
-typedef unsigned int u32;
 
 constexpr int kFrag = 1024;          // bytes of one 32x32 int8 fragment
 
 template <class T> __device__ inline T digit_bias();
+template <> __device__ inline u32 digit_bias<u32>() { return 0x80808080u; }
 template <> __device__ inline u64 digit_bias<u64>() { return 0x8080808080808080ull; }
 template <> __device__ inline u128 digit_bias<u128>()
 {
@@ -69,9 +69,9 @@ template <class T> struct PackArgs {
 // accumulates in registers while each triple share is converted and stored as it arrives.  Slots:
 // 0 = opened, 1 + i = party i's triple share (left side A_i; right side B_i, and for party 0 B_0 + F,
 // which folds the public E.F term into party 0's first product).  One wave handles one 32 x 32 tile
-// (blk, kt); blockIdx.z = batch.  Party 0's triple share is needed again at the end (B_0 + F): 8-byte
-// rings keep it in registers, 16-byte rings read it a second time (KEEP = false) to stay within the
-// register file.
+// (blk, kt); blockIdx.z = batch.  Party 0's triple share is needed again at the end (B_0 + F): rings of
+// up to 8 bytes keep it in registers, 16-byte rings read it a second time (KEEP = false) to stay within
+// the register file.
 
 // Right side: source K x N row-major, a fragment row is a matrix column, so the 16 consecutive k a
 // lane needs are 16 strided loads whose lanes run along contiguous columns.
@@ -79,7 +79,7 @@ template <int NP, class T>
 __global__ __launch_bounds__(256) void pack_right_kernel(PackArgs<T> a)
 {
     constexpr int ND = sizeof(T);
-    constexpr bool KEEP = sizeof(T) == 8;
+    constexpr bool KEEP = sizeof(T) <= 8;
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const long tile = (long)blockIdx.x * 4 + wave;
     if (tile >= (long)a.nblk * a.KT) return;
@@ -146,11 +146,11 @@ template <int NP, class T, bool VEC, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void pack_left_kernel(PackArgs<T> a)
 {
     constexpr int ND = sizeof(T);
-    constexpr bool KEEP = sizeof(T) == 8;
-    constexpr int EPL = 16 / ND;                 // elements per 16-byte lane load: 2 or 1
-    constexpr int LPR = 32 / EPL;                // lanes that cover the 32 k of one row: 16 or 32
-    constexpr int RPL = 64 / LPR;                // rows per wave-wide load: 4 or 2
-    constexpr int NL = 32 / RPL;                 // loads per lane: 8 or 16
+    constexpr bool KEEP = sizeof(T) <= 8;
+    constexpr int EPL = 16 / ND;                 // elements per 16-byte lane load: 4, 2 or 1
+    constexpr int LPR = 32 / EPL;                // lanes that cover the 32 k of one row: 8, 16 or 32
+    constexpr int RPL = 64 / LPR;                // rows per wave-wide load: 8, 4 or 2
+    constexpr int NL = 32 / RPL;                 // loads per lane: 4, 8 or 16
     constexpr int kRowBytes = 32 * ND + 16;
     struct alignas(16) Pair { T e[EPL]; };
     __shared__ __attribute__((aligned(16))) char turn[WAVES][32 * kRowBytes];
@@ -290,7 +290,7 @@ inline void launch_pack(const MatmulArgsT<T> &a, char *packA, char *packB, int n
 {
     PackArgs<T> pa{a.X, a.A, packA, a.n, a.batch, a.M, a.K, nblkA, KT};
     PackArgs<T> pb{a.Y, a.B, packB, a.n, a.batch, a.K, a.N, nblkB, KT};
-    constexpr int WAVES = sizeof(T) == 8 ? 4 : 2;
+    constexpr int WAVES = sizeof(T) <= 8 ? 4 : 2;
     constexpr int EPL = 16 / sizeof(T);
     for_party_count(a.n, [&](auto np) {
         constexpr int NP = decltype(np)::value;

@@ -282,6 +282,76 @@ spin_status spin128_trunc(int n, size_t count, int f, const uint64_t *x, const u
     return launch_trunc<u128>(n, count, f, r128(x), r128(r), r128(r_top), r128(r_msb), r128(out), (hipStream_t)stream);
 }
 
+// ---- Z_2^32 --------------------------------------------------------------------------------
+spin_status spin32_share(const uint32_t *x, size_t count, int n, uint64_t seed, uint64_t stream_id,
+                         uint32_t *shares, spin_stream stream)
+{
+    if (bad_ptr(x) || bad_ptr(shares) || bad_n(n) || count == 0) return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    PartyKeys keys;
+    for (int i = 0; i < SPIN_MAX_PARTIES; ++i) keys.key[i] = stream_key(seed, stream_id, (u64)i);
+    return launch_share32(x, count, n, keys, shares, (hipStream_t)stream);
+}
+
+spin_status spin32_open(const uint32_t *shares, const uint32_t *mask, size_t count, int n, uint32_t *out,
+                        spin_stream stream)
+{
+    if (bad_ptr(shares) || bad_ptr(out) || (mask && !aligned16(mask)) || bad_n(n) || count == 0)
+        return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    return launch_open<u32>(shares, mask, count, n, out, (hipStream_t)stream);
+}
+
+size_t spin32_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path)
+{
+    if (check_matmul_dims(n, batch, M, N, K) != SPIN_OK) return 0;
+    if (path == SPIN_GEMM_LIMB_MFMA) return limb32_workspace_bytes(n, batch, M, N, K);
+    if (path == SPIN_GEMM_VALU) return valu_workspace_bytes(n, batch, M, N, K, 4);
+    return 0;
+}
+
+spin_status spin32_beaver_matmul(int n, int batch, int M, int N, int K, const uint32_t *X, const uint32_t *Y,
+                                 const uint32_t *A, const uint32_t *B, const uint32_t *C, uint32_t *Z,
+                                 spin_gemm_path path, void *workspace, size_t workspace_bytes, spin_stream stream)
+{
+    if (bad_ptr(X) || bad_ptr(Y) || bad_ptr(A) || bad_ptr(B) || bad_ptr(C) || bad_ptr(Z)) return SPIN_EINVAL;
+    if (path != SPIN_GEMM_LIMB_MFMA && path != SPIN_GEMM_VALU) return SPIN_EINVAL;
+    spin_status st = check_matmul_dims(n, batch, M, N, K);
+    if (st != SPIN_OK) return st;
+    const size_t need = spin32_beaver_matmul_workspace_bytes(n, batch, M, N, K, path);
+    if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need)
+        return SPIN_EWORKSPACE;
+    MatmulArgs32 a{n, batch, M, N, K, X, Y, A, B, C, Z, workspace};
+    return path == SPIN_GEMM_LIMB_MFMA ? launch_matmul_limb32(a, (hipStream_t)stream)
+                                       : launch_matmul_valu<u32>(a, (hipStream_t)stream);
+}
+
+spin_status spin32_beaver_mul(int n, size_t count, const uint32_t *x, const uint32_t *y, const uint32_t *a,
+                              const uint32_t *b, const uint32_t *c, uint32_t *z, spin_stream stream)
+{
+    if (bad_ptr(x) || bad_ptr(y) || bad_ptr(a) || bad_ptr(b) || bad_ptr(c) || bad_ptr(z) || bad_n(n) || count == 0)
+        return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    return launch_beaver_mul<u32>(n, count, x, y, a, b, c, z, (hipStream_t)stream);
+}
+
+spin_status spin32_trunc(int n, size_t count, int f, const uint32_t *x, const uint32_t *r, const uint32_t *r_top,
+                         const uint32_t *r_msb, uint32_t *out, spin_stream stream)
+{
+    if (bad_ptr(x) || bad_ptr(r) || bad_ptr(r_top) || bad_ptr(r_msb) || bad_ptr(out) || bad_n(n) || count == 0)
+        return SPIN_EINVAL;
+    if (f < 1 || f > 29) return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    return launch_trunc<u32>(n, count, f, x, r, r_top, r_msb, out, (hipStream_t)stream);
+}
+
+spin_status spin_cast_64_to_32(const uint64_t *in, size_t count, uint32_t *out, spin_stream stream)
+{
+    if (bad_ptr(in) || bad_ptr(out) || count == 0) return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    return launch_cast_low(in, count, out, (hipStream_t)stream);
+}
+
 const char *spin_status_string(spin_status status)
 {
     switch (status) {

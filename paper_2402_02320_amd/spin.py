@@ -62,6 +62,17 @@ def lib():
         L.spin128_trunc.argtypes = L.spin_trunc.argtypes
         for name in ("spin128_share", "spin128_open", "spin128_beaver_matmul", "spin128_beaver_mul", "spin128_trunc"):
             getattr(L, name).restype = i32
+        L.spin32_share.argtypes = L.spin_share.argtypes
+        L.spin32_open.argtypes = L.spin_open.argtypes
+        L.spin32_beaver_matmul.argtypes = L.spin_beaver_matmul.argtypes
+        L.spin32_beaver_matmul_workspace_bytes.argtypes = L.spin_beaver_matmul_workspace_bytes.argtypes
+        L.spin32_beaver_matmul_workspace_bytes.restype = sz
+        L.spin32_beaver_mul.argtypes = L.spin_beaver_mul.argtypes
+        L.spin32_trunc.argtypes = L.spin_trunc.argtypes
+        L.spin_cast_64_to_32.argtypes = [p, sz, p, p]
+        for name in ("spin32_share", "spin32_open", "spin32_beaver_matmul", "spin32_beaver_mul", "spin32_trunc",
+                     "spin_cast_64_to_32"):
+            getattr(L, name).restype = i32
         L.spin_status_string.argtypes = [i32]
         L.spin_status_string.restype = ctypes.c_char_p
         L.spin_last_hip_error.restype = ctypes.c_char_p
@@ -281,8 +292,87 @@ class ring128:
         return out
 
 
+def _dev32(t, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+        raise SpinError("%s must be a contiguous torch.int32 CUDA tensor" % name)
+    return t.data_ptr()
+
+
+class ring32:
+    """The same calls over Z_2^32 (the Fixed32 representation of Section 7.1).  Ring tensors are
+    torch.int32 CUDA tensors (the bit pattern of a uint32 ring element), party-major."""
+
+    @staticmethod
+    def cast_from_64(shares, out=None):
+        """Local Fixed64 -> Fixed32 cast: every party keeps the low half of its own share."""
+        if out is None:
+            out = torch.empty(tuple(shares.shape), dtype=torch.int32, device=shares.device)
+        _check(lib().spin_cast_64_to_32(_dev(shares, "shares"), shares.numel(), _dev32(out, "out"), _stream()))
+        return out
+
+    @staticmethod
+    def share(x, n, seed, stream_id, out=None):
+        if out is None:
+            out = torch.empty((n,) + tuple(x.shape), dtype=torch.int32, device=x.device)
+        _check(lib().spin32_share(_dev32(x, "x"), x.numel(), n, seed, stream_id, _dev32(out, "shares"), _stream()))
+        return out
+
+    @staticmethod
+    def open(shares, mask=None, out=None):  # noqa: A003
+        n = shares.shape[0]
+        if out is None:
+            out = torch.empty(tuple(shares.shape[1:]), dtype=torch.int32, device=shares.device)
+        if mask is not None and mask.shape != shares.shape:
+            raise SpinError("mask must have the shape of shares")
+        _check(lib().spin32_open(_dev32(shares, "shares"), None if mask is None else _dev32(mask, "mask"),
+                                 out.numel(), n, _dev32(out, "out"), _stream()))
+        return out
+
+    @staticmethod
+    def beaver_matmul_workspace_bytes(n, batch, M, N, K, path=LIMB_MFMA):
+        return int(lib().spin32_beaver_matmul_workspace_bytes(n, batch, M, N, K, path))
+
+    @staticmethod
+    def beaver_matmul(X, Y, A, B, C, path=LIMB_MFMA, out=None, workspace=None):
+        n, batch, M, K = X.shape
+        N = Y.shape[3]
+        if tuple(Y.shape) != (n, batch, K, N) or A.shape != X.shape or B.shape != Y.shape \
+                or tuple(C.shape) != (n, batch, M, N):
+            raise SpinError("inconsistent operand shapes")
+        if out is None:
+            out = torch.empty_like(C)
+        need = ring32.beaver_matmul_workspace_bytes(n, batch, M, N, K, path)
+        if need == 0:
+            raise SpinError("invalid matmul dimensions")
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
+        _check(lib().spin32_beaver_matmul(n, batch, M, N, K, _dev32(X, "X"), _dev32(Y, "Y"), _dev32(A, "A"),
+                                          _dev32(B, "B"), _dev32(C, "C"), _dev32(out, "Z"), path,
+                                          workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                          _stream()))
+        return out
+
+    @staticmethod
+    def beaver_mul(x, y, a, b, c, out=None):
+        n = x.shape[0]
+        if out is None:
+            out = torch.empty_like(x)
+        _check(lib().spin32_beaver_mul(n, x[0].numel(), _dev32(x, "x"), _dev32(y, "y"), _dev32(a, "a"),
+                                       _dev32(b, "b"), _dev32(c, "c"), _dev32(out, "z"), _stream()))
+        return out
+
+    @staticmethod
+    def trunc(x, r, r_top, r_msb, f, out=None):
+        n = x.shape[0]
+        if out is None:
+            out = torch.empty_like(x)
+        _check(lib().spin32_trunc(n, x[0].numel(), f, _dev32(x, "x"), _dev32(r, "r"), _dev32(r_top, "r_top"),
+                                  _dev32(r_msb, "r_msb"), _dev32(out, "out"), _stream()))
+        return out
+
+
 KERNELS = {"random": 0, "share": 1, "open": 2, "beaver_mul": 3, "trunc": 4, "pack": 5, "gemm_limb": 6,
-           "gemm_valu": 7, "lincomb": 8, "binary": 9}
+           "gemm_valu": 7, "lincomb": 8, "binary": 9, "cast": 10}
 
 
 def profile_enable(on=True):

@@ -97,3 +97,26 @@ def test_status_strings(L):
     assert L.spin_status_string(0) == b"ok"
     assert b"workspace" in L.spin_status_string(3)
     assert L.spin_last_hip_error() == b""
+
+
+def test_validation_of_the_32_bit_entry_points(L):
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    EINVAL, ERANGE, EWORKSPACE = 1, 2, 3
+    assert L.spin32_share(fake, 8, 9, 1, 1, fake, None) == EINVAL
+    assert L.spin32_share(odd, 8, 2, 1, 1, fake, None) == EINVAL
+    assert L.spin32_open(fake, None, 0, 2, fake, None) == EINVAL
+    assert L.spin32_trunc(2, 8, 30, fake, fake, fake, fake, fake, None) == EINVAL
+    assert L.spin32_trunc(2, 8, 0, fake, fake, fake, fake, fake, None) == EINVAL
+    assert L.spin32_beaver_mul(2, 8, fake, fake, None, fake, fake, fake, None) == EINVAL
+    assert L.spin_cast_64_to_32(fake, 0, fake, None) == EINVAL
+    assert L.spin_cast_64_to_32(None, 8, fake, None) == EINVAL
+    assert L.spin_cast_64_to_32(fake, 1 << 40, fake, None) == ERANGE
+    mm = L.spin32_beaver_matmul
+    assert mm(2, 1, 4, 4, 4, fake, fake, fake, fake, fake, fake, 0, None, 0, None) == EWORKSPACE
+    assert mm(2, 1, 4, 0, 4, fake, fake, fake, fake, fake, fake, 0, fake, 1 << 30, None) == EINVAL
+    q = L.spin32_beaver_matmul_workspace_bytes
+    assert q(3, 2, 10, 7, 5, 1) == 4 * 2 * (10 * 5 + 5 * 7)
+    # limb path: n+1 digit-fragment copies of the operands padded to 128 x 128 tiles, 4 bytes per element
+    assert q(2, 1, 1024, 1024, 1024, 0) == 4 * 3 * (1024 * 1024 * 2)
+    assert q(2, 1, 100, 100, 100, 0) == 4 * 3 * (128 * 128 * 2)
