@@ -259,23 +259,46 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
     iteration(B0(), F(), Y(), F());                       // step steps-2
     iteration(B1(), F(), F(), F());                       // step steps-1
 
-    // recombine the diagonals and add C_i
+    // Recombine the diagonals and add C_i.  The 16 C values of a lane in one MFMA tile are loaded before
+    // the first of its stores: interleaved, every load would wait out the store before it (C and Z may
+    // be the same buffer, so the compiler keeps their order), 32 memory round trips in a row with
+    // nothing else on the CU.
+    // Tiles that lie wholly inside the matrix take branch-free loads and stores: with a bounds check per
+    // element every store sits in a basic block of its own and again waits for the one before.  Only
+    // the memory accesses are duplicated; the arithmetic between them is shared by both cases.
     const size_t mat = (size_t)g.M * g.N;
     const T *Cm = g.C + (size_t)pb * mat;
     T *Zm = g.Z + (size_t)pb * mat;
+    const bool interior = (tm + 1) * S::BM <= g.M && (tn + 1) * S::BN <= g.N;     // uniform over the workgroup
 #pragma unroll
     for (int i = 0; i < WM; ++i)
 #pragma unroll
-        for (int j = 0; j < WN; ++j) {
+        for (int j = 0; j < WN; ++j) {                   // one 32 x 32 MFMA tile at a time
             const int col = tn * S::BN + (wn * WN + j) * 32 + lane % 32;
             const int row0 = tm * S::BM + (wm * WM + i) * 32 + 4 * (lane / 32);
+            auto row_of = [&](int r) { return row0 + 8 * (r / 4) + r % 4; };
+            T v[16];
+            __builtin_amdgcn_sched_barrier(0);           // keeps the scheduler from hoisting the next tile's work
+            if (interior) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + 8 * (r / 4) + r % 4;
-                T v = 0;
+                for (int r = 0; r < 16; ++r) v[r] = Cm[(size_t)row_of(r) * g.N + col];
+            } else {
 #pragma unroll
-                for (int d = 0; d < kDigits; ++d) v += (T)(int64_t)acc[i][j][d][r] << (8 * d);
-                if (row < g.M && col < g.N) Zm[(size_t)row * g.N + col] = Cm[(size_t)row * g.N + col] + v;
+                for (int r = 0; r < 16; ++r)
+                    v[r] = (row_of(r) < g.M && col < g.N) ? Cm[(size_t)row_of(r) * g.N + col] : (T)0;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+#pragma unroll
+                for (int d = 0; d < kDigits; ++d) v[r] += (T)(int64_t)acc[i][j][d][r] << (8 * d);
+            if (interior) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) Zm[(size_t)row_of(r) * g.N + col] = v[r];
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (row_of(r) < g.M && col < g.N) Zm[(size_t)row_of(r) * g.N + col] = v[r];
             }
         }
 }

@@ -135,20 +135,33 @@ __global__ __launch_bounds__(256) void limb128_gemm_kernel(Gemm128Args g)
         if (more) advance_load_cursor();
     }
 
-    // recombine the diagonals and add C_i
+    // Recombine the diagonals and add C_i.  All C values are loaded before the first store, so that the
+    // loads do not each wait out the store before them (C and Z may be the same buffer); tiles wholly
+    // inside the matrix take a branch-free copy, in which the stores do not wait for each other either.
     const size_t mat = (size_t)g.M * g.N;
     const u128 *Cm = g.C + (size_t)pb * mat;
     u128 *Zm = g.Z + (size_t)pb * mat;
     const int col = tn * S::BN + wn * 32 + lane % 32;
     const int row0 = tm * S::BM + wm * 32 + 4 * (lane / 32);
+    auto epilogue = [&](auto interior_c) {
+        constexpr bool INTERIOR = decltype(interior_c)::value;
+        u128 cv[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int row = row0 + 8 * (r / 4) + r % 4;
-        u128 v = 0;
+        for (int r = 0; r < 16; ++r) {
+            const int row = row0 + 8 * (r / 4) + r % 4;
+            cv[r] = (INTERIOR || (row < g.M && col < g.N)) ? Cm[(size_t)row * g.N + col] : (u128)0;
+        }
 #pragma unroll
-        for (int d = 0; d < ND; ++d) v += (u128)(__int128)acc[d][r] << (8 * d);
-        if (row < g.M && col < g.N) Zm[(size_t)row * g.N + col] = Cm[(size_t)row * g.N + col] + v;
-    }
+        for (int r = 0; r < 16; ++r) {
+            const int row = row0 + 8 * (r / 4) + r % 4;
+            u128 v = cv[r];
+#pragma unroll
+            for (int d = 0; d < ND; ++d) v += (u128)(__int128)acc[d][r] << (8 * d);
+            if (INTERIOR || (row < g.M && col < g.N)) Zm[(size_t)row * g.N + col] = v;
+        }
+    };
+    if ((tm + 1) * S::BM <= g.M && (tn + 1) * S::BN <= g.N) epilogue(std::true_type());
+    else epilogue(std::false_type());
 }
 
 struct Plan128 {

@@ -73,18 +73,24 @@ __global__ __launch_bounds__(256) void valu_gemm_kernel(int n, int batch, int M,
         }
         __syncthreads();
     }
+    // all C values are loaded before the first store (C and Z may be the same buffer, so interleaved
+    // loads would each wait out the store before them)
     const T *Ci = C + (size_t)pb * M * N;
     T *Zi = Z + (size_t)pb * M * N;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int gm = m0 + ty * 4 + i;
-        if (gm >= M) continue;
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            int gn = n0 + tx * 4 + j;
-            if (gn < N) Zi[(size_t)gm * N + gn] = Ci[(size_t)gm * N + gn] + acc[i][j];
+            int gm = m0 + ty * 4 + i, gn = n0 + tx * 4 + j;
+            if (gm < M && gn < N) acc[i][j] += Ci[(size_t)gm * N + gn];
         }
-    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int gm = m0 + ty * 4 + i, gn = n0 + tx * 4 + j;
+            if (gm < M && gn < N) Zi[(size_t)gm * N + gn] = acc[i][j];
+        }
 }
 
 }  // namespace
