@@ -38,6 +38,9 @@ def parse():
                     help="matmul: the Beaver-matmul hot path (the benchmark); poly: completed-square polynomial "
                          "evaluation (Section 7.2 Eq. (4)) on the configuration's vector length; matmul128 / matmul32: the "
                          "Beaver matmul over the other two ring widths")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time its replays (for the launch-bound small "
+                         "configurations; the per-kernel figures then come from a separate eager pass)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
@@ -292,14 +295,38 @@ def main():
         step()
     torch.cuda.synchronize()
     spin.profile_reset()
-    spin.profile_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    spin.profile_enable(False)
+    if args.graph:
+        # event pairs cannot be recorded into a captured graph: per-kernel durations come from an eager pass
+        # first, the timed region replays the captured step
+        spin.profile_enable(True)
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        spin.profile_enable(False)
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    else:
+        spin.profile_enable(True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        spin.profile_enable(False)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     ring_macs = 2.0 * n * batch * M * N * K
@@ -345,7 +372,7 @@ def main():
         "config": {"workload": "config %d: %d parties, batch %d, M=%d N=%d K=%d, f=%d, %s; step = share X,Y + Beaver "
                                "matmul (open+update) + trunc + elementwise Beaver mul + trunc" %
                                (args.config, n, batch, M, N, K, f, c.dist),
-                   "gemm_path": args.path, "parties": n},
+                   "gemm_path": args.path, "parties": n, "launch": "hip graph replay" if args.graph else "eager"},
         "roofline": roofline, "stream_kernels": streams,
         "limb_roofline_ring_mac_per_s": PEAK_INT8_TOPS * 1e12 / INT8_OPS_PER_RING_MAC,
     }
