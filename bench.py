@@ -92,9 +92,17 @@ def cpu_baseline(cfg, target_s):
     t = run(nrows)
     macs = (2 * c.n + 1) * batch * nrows * N * K     # the oracle also forms E.F explicitly for party 0
     credited = 2 * c.n * batch * nrows * N * K
+    # per-core figure: the row loop alone on one thread (the opening is subtracted through a second run)
+    oracle.set_threads(1)
+    r1 = max(1, nrows // (4 * threads))
+    t_a, t_b = run(r1), run(2 * r1)
+    oracle.set_threads(threads)
+    one_core = 2 * c.n * batch * r1 * N * K / max(t_b - t_a, 1e-9)
     return {"value": credited / t, "unit": "ring MAC/s", "cores": threads, "kind": "oracle",
             "sample": "config %d, %d of %d output rows of every party's share (%.1f s, incl. opening E and F; "
-                      "%.3g ring MACs executed, %.3g credited as n*2*rows*N*K)" % (cfg, nrows, M, t, macs, credited)}
+                      "%.3g ring MACs executed, %.3g credited as n*2*rows*N*K)" % (cfg, nrows, M, t, macs, credited),
+            "one_core_value": one_core,
+            "one_core_sample": "row loop on 1 thread: time of %d rows minus time of %d rows" % (2 * r1, r1)}
 
 
 def bench_poly(args):
@@ -318,15 +326,20 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+        step_ms = None
     else:
         spin.profile_enable(True)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
+        marks[0].record()
+        for i in range(args.steps):
             step()
+            marks[i + 1].record()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         spin.profile_enable(False)
+        step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     ring_macs = 2.0 * n * batch * M * N * K
@@ -374,6 +387,7 @@ def main():
                                (args.config, n, batch, M, N, K, f, c.dist),
                    "gemm_path": args.path, "parties": n, "launch": "hip graph replay" if args.graph else "eager"},
         "roofline": roofline, "stream_kernels": streams,
+        "step_ms_median": step_ms[len(step_ms) // 2] if step_ms else None, "step_ms_min": step_ms[0] if step_ms else None,
         "limb_roofline_ring_mac_per_s": PEAK_INT8_TOPS * 1e12 / INT8_OPS_PER_RING_MAC,
     }
     if not args.no_cpu_baseline:

@@ -103,6 +103,10 @@ def threads():
     return int(lib().oracle_threads())
 
 
+def set_threads(t):
+    lib().oracle_set_threads(int(t))
+
+
 def rand64(seed, stream, party, idx):
     return int(lib().oracle_rand64(seed, stream, party, idx))
 

@@ -334,12 +334,15 @@ void oracle_local_shift_trunc(int n, size_t count, int f, const u64 *x, u64 *out
         }
 }
 
-/* Number of threads the row loops actually run on (for the benchmark report). */
+/* Number of threads the row loops actually run on, and a way to fix it (for the benchmark report's
+ * all-cores and single-core figures). */
 #ifdef _OPENMP
 #include <omp.h>
 int oracle_threads(void) { return omp_get_max_threads(); }
+void oracle_set_threads(int t) { if (t >= 1) omp_set_num_threads(t); }
 #else
 int oracle_threads(void) { return 1; }
+void oracle_set_threads(int t) { (void)t; }
 #endif
 
 /* One generator step, exposed so the tests can hold it against the published
