@@ -68,30 +68,37 @@ template <class T> struct PackArgs {
 // Both pack kernels make one pass over the 2n share streams of their side: the opened matrix (E or F)
 // accumulates in registers while each triple share is converted and stored as it arrives.  Slots:
 // 0 = opened, 1 + i = party i's triple share (left side A_i; right side B_i, and for party 0 B_0 + F,
-// which folds the public E.F term into party 0's first product).  One wave handles one 32 x 32 tile
-// (blk, kt); blockIdx.z = batch.  Party 0's triple share is needed again at the end (B_0 + F): rings of
+// which folds the public E.F term into party 0's first product).  blockIdx.z = batch.  Party 0's triple share is needed again at the end (B_0 + F): rings of
 // up to 8 bytes keep it in registers, 16-byte rings read it a second time (KEEP = false) to stay within
 // the register file.
 
 // Right side: source K x N row-major, a fragment row is a matrix column, so the 16 consecutive k a
-// lane needs are 16 strided loads whose lanes run along contiguous columns.
+// lane needs are 16 strided loads whose lanes run along contiguous columns.  One wave handles 64
+// columns x 16 k (half a k-tile of two adjacent column blocks): every wave-wide load is one contiguous
+// 64-element row segment, every store two contiguous half-fragment chunks; consecutive waves continue
+// along the row.
 template <int NP, class T>
 __global__ __launch_bounds__(256) void pack_right_kernel(PackArgs<T> a)
 {
     constexpr int ND = sizeof(T);
     constexpr bool KEEP = sizeof(T) <= 8;
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-    const long tile = (long)blockIdx.x * 4 + wave;
-    if (tile >= (long)a.nblk * a.KT) return;
-    const int blk = (int)(tile / a.KT), kt = (int)(tile % a.KT);
+    const int nblk2 = (a.nblk + 1) / 2;                    // pairs of column blocks
+    const long tile = (long)blockIdx.x * 4 + wave;         // (kt, half, block pair), block pair fastest
+    if (tile >= (long)nblk2 * a.KT * 2) return;
+    const int blk2 = (int)(tile % nblk2);
+    const int half = (int)(tile / nblk2 % 2), kt = (int)(tile / nblk2 / 2);
+    const int blk = blk2 * 2 + lane / 32;
     const int b = blockIdx.z;
     const int K = a.rows, N = a.cols;
-    const int col = blk * 32 + (lane % 32);
-    const int k0 = kt * 32 + 16 * (lane / 32);
+    const int col = blk2 * 64 + lane;
+    const int k0 = kt * 32 + 16 * half;
+    const bool owns = blk < a.nblk;                        // the last pair may have only one block
     const size_t mat = (size_t)K * N;
     const size_t party_stride = (size_t)a.batch * mat;
     auto frag = [&](int slot) -> char * {
-        return a.pack + ((((size_t)slot * a.batch + b) * a.nblk + blk) * a.KT + kt) * (ND * kFrag) + lane * 16;
+        return a.pack + ((((size_t)slot * a.batch + b) * a.nblk + blk) * a.KT + kt) * (ND * kFrag) +
+               (lane % 32 + 32 * half) * 16;
     };
     T opened[16], first[KEEP ? 16 : 1];
 #pragma unroll
@@ -100,15 +107,21 @@ __global__ __launch_bounds__(256) void pack_right_kernel(PackArgs<T> a)
     for (int i = 0; i < NP; ++i) {
         const T *v = a.val + (size_t)i * party_stride + (size_t)b * mat;
         const T *t = a.tri + (size_t)i * party_stride + (size_t)b * mat;
-        T tv[16];
+        // Loads are unconditional (an out-of-range element reads element 0 and is replaced by zero):
+        // guarded by a branch each, every load would be awaited before the next one is issued.
+        T tv[16], xv[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            tv[j] = 0;
-            if (col < N && k0 + j < K) {
-                const size_t e = (size_t)(k0 + j) * N + col;
-                tv[j] = t[e];
-                opened[j] += v[e] - tv[j];
-            }
+            const bool ok = col < N && k0 + j < K;
+            const size_t e = ok ? (size_t)(k0 + j) * N + col : 0;
+            tv[j] = t[e];
+            xv[j] = v[e];
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const bool ok = col < N && k0 + j < K;
+            tv[j] = ok ? tv[j] : (T)0;
+            opened[j] += ok ? xv[j] - tv[j] : (T)0;
         }
         if (i == 0) {
             if (KEEP) {
@@ -118,27 +131,32 @@ __global__ __launch_bounds__(256) void pack_right_kernel(PackArgs<T> a)
         } else {
 #pragma unroll
             for (int j = 0; j < 16; ++j) tv[j] = to_digits<T>(tv[j]);
-            store_digit_rows<T>(tv, frag(i + 1));
+            if (owns) store_digit_rows<T>(tv, frag(i + 1));
         }
     }
     T w[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) w[j] = to_digits<T>(opened[j]);
-    store_digit_rows<T>(w, frag(0));
+    if (owns) store_digit_rows<T>(w, frag(0));
     const T *t0 = a.tri + (size_t)b * mat;
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
         T f0 = 0;
-        if (KEEP) f0 = first[j];
-        else if (col < N && k0 + j < K) f0 = t0[(size_t)(k0 + j) * N + col];
+        if (KEEP) {
+            f0 = first[j];
+        } else {
+            const bool ok = col < N && k0 + j < K;
+            f0 = t0[ok ? (size_t)(k0 + j) * N + col : 0];
+            f0 = ok ? f0 : (T)0;
+        }
         w[j] = to_digits<T>(f0 + opened[j]);
     }
-    store_digit_rows<T>(w, frag(1));
+    if (owns) store_digit_rows<T>(w, frag(1));
 }
 
 // Left side: source M x K row-major, a fragment row is a matrix row.  Reading 16 consecutive k per
 // lane directly would make every wave-wide load touch 64 different rows; instead a wave reads its
-// tile as whole-row segments (16 bytes per lane, 32 k of one row contiguous), sums the parties'
+// 32 x 32 tile (blk, kt) as whole-row segments (16 bytes per lane, 32 k of one row contiguous), sums the parties'
 // shares in that layout, and turns each 32 x 32 tile through LDS (rows padded by 16 bytes,
 // conflict-free for 16-byte accesses both ways) so that each lane ends up with the 16 consecutive k
 // of one row that a fragment chunk needs.  WAVES = waves per block (LDS: WAVES x 32 padded rows).
@@ -167,16 +185,22 @@ __global__ __launch_bounds__(64 * WAVES) void pack_left_kernel(PackArgs<T> a)
     auto frag = [&](int slot) -> char * {
         return a.pack + ((((size_t)slot * a.batch + b) * a.nblk + blk) * a.KT + kt) * (ND * kFrag) + lane * 16;
     };
-    auto load = [&](const T *base, int row) -> Pair {       // elements (row, kk ..), zero outside
+    // elements (row, kk ..), zero outside.  The loads themselves are unconditional (an out-of-range
+    // element reads element 0 of the matrix and is replaced by zero), so that none of them sits behind
+    // a branch and has to be awaited before the next is issued.
+    auto load = [&](const T *base, int row) -> Pair {
         Pair v;
+        if (VEC) {
+            const bool ok = row < M && kk < K;
+            v = *(const Pair *)(base + (ok ? (size_t)row * K + kk : 0));
 #pragma unroll
-        for (int q = 0; q < EPL; ++q) v.e[q] = 0;
-        if (row < M) {
-            const T *p = base + (size_t)row * K + kk;
-            if (VEC) { if (kk < K) v = *(const Pair *)p; }
-            else {
+            for (int q = 0; q < EPL; ++q) v.e[q] = ok ? v.e[q] : (T)0;
+        } else {
 #pragma unroll
-                for (int q = 0; q < EPL; ++q) if (kk + q < K) v.e[q] = p[q];
+            for (int q = 0; q < EPL; ++q) {
+                const bool ok = row < M && kk + q < K;
+                const T x = base[ok ? (size_t)row * K + kk + q : 0];
+                v.e[q] = ok ? x : (T)0;
             }
         }
         return v;
@@ -298,7 +322,7 @@ inline void launch_pack(const MatmulArgsT<T> &a, char *packA, char *packB, int n
         dim3 ga((unsigned)(((long)nblkA * KT + WAVES - 1) / WAVES), 1, a.batch);
         if (a.K % EPL == 0) pack_left_kernel<NP, T, true, WAVES><<<ga, 64 * WAVES, 0, s>>>(pa);   // rows 16-byte aligned
         else pack_left_kernel<NP, T, false, WAVES><<<ga, 64 * WAVES, 0, s>>>(pa);
-        dim3 gb((unsigned)(((long)nblkB * KT + 3) / 4), 1, a.batch);
+        dim3 gb((unsigned)(((long)((nblkB + 1) / 2) * KT * 2 + 3) / 4), 1, a.batch);
         pack_right_kernel<NP, T><<<gb, 256, 0, s>>>(pb);
     });
 }
