@@ -22,7 +22,8 @@ __global__ __launch_bounds__(256) void valu_gemm_kernel(int n, int batch, int M,
 
     const int pb = blockIdx.z;          // party * batch + b
     const int party = pb / batch, b = pb % batch;
-    const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+    const int tiles_n = (N + TN - 1) / TN;           // blockIdx.x = tile row * tiles_n + tile column
+    const int m0 = (int)(blockIdx.x / tiles_n) * TM, n0 = (int)(blockIdx.x % tiles_n) * TN;
     const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
 
     const T *Eb = E + (size_t)b * M * K;
@@ -109,7 +110,8 @@ template <class T> spin_status launch_matmul_valu(const MatmulArgsT<T> &a, hipSt
     st = launch_open<T>(a.Y, a.B, (size_t)a.batch * a.K * a.N, a.n, F, s);
     if (st != SPIN_OK) return st;
     KernelTimer timer(SPIN_KERNEL_GEMM_VALU, s);
-    dim3 grid((a.N + TN - 1) / TN, (a.M + TM - 1) / TM, a.n * a.batch);
+    // tiles on the x axis (the y axis holds at most 65535 blocks, fewer than the tile rows of a long operand)
+    dim3 grid((unsigned)((size_t)((a.N + TN - 1) / TN) * ((a.M + TM - 1) / TM)), 1, a.n * a.batch);
     valu_gemm_kernel<T><<<grid, 256, 0, s>>>(a.n, a.batch, a.M, a.N, a.K, E, F, a.A, a.B, a.C, a.Z);
     return check_launch("spin_beaver_matmul(valu)");
 }

@@ -142,6 +142,14 @@ def test_beaver_matmul_in_place_on_c(path):
     assert (host(Cd) == oracle.beaver_matmul(X, Y, A, B, C)).all()
 
 
+@pytest.mark.parametrize("path", PATHS)
+def test_tall_operand_with_more_tile_rows_than_a_grid_axis_holds(path):
+    # 65537 tile rows of 64 (VALU path) exceed the 65535 blocks of a grid's y and z axes
+    M = 65536 * 64 + 1
+    got, want = matmul_case(2, 1, M, 3, 2, seed=21, path=path)
+    assert (got == want).all()
+
+
 def test_limb_path_worst_case_digits_and_inner_dimension_split():
     # every digit of every operand equal to -128 (value 0x7F7F7F7F7F7F7F80), with K large enough that
     # the inner dimension is split into more than one accumulation chunk: the int32 partial sums run
