@@ -61,6 +61,35 @@ def measured_traffic(kernel, cfg):
     return None
 
 
+def mfma_ceiling(kernel_tops):
+    """The int8 MFMA rate this chip sustains on this machine, from a register-only loop of the GEMM's MFMA
+    pattern (spin_probe_mfma): on all-zero operands and on uniformly random operand bytes, which is what the
+    digits of masked shares are.  The published peak stays the roofline; these two figures say how much of
+    the gap to it is the chip's clock under this data rather than the kernel."""
+    import torch
+    from paper_2402_02320_amd import spin
+    blocks, iters = 1024, 2000
+    sink = torch.empty(blocks * 256, dtype=torch.int64, device="cuda")
+    res = {}
+    for name, ops in (("zero_operands", torch.zeros(24 * 128, dtype=torch.int64, device="cuda")),
+                      ("random_operands", spin.random(24 * 128, 0x5350494E, 99, 0))):
+        spin.probe_mfma(ops, blocks, iters, sink)                # warm-up
+        torch.cuda.synchronize()
+        spin.profile_reset()
+        spin.profile_enable(True)
+        for _ in range(3):
+            spin.probe_mfma(ops, blocks, iters, sink)
+        torch.cuda.synchronize()
+        spin.profile_enable(False)
+        ms, cnt = spin.profile_read("probe")
+        spin.profile_reset()
+        tops = blocks * 4 * iters * spin.PROBE_OPS_PER_WAVE_ITERATION / (ms / cnt * 1e-3) / 1e12
+        res[name] = {"TOP/s": tops, "frac_of_peak": tops / PEAK_INT8_TOPS}
+    res["kernel_over_random_ceiling"] = kernel_tops / res["random_operands"]["TOP/s"]
+    res["what"] = "register-only loop of the limb GEMM's 72-MFMA k-step, 1024 workgroups x 2000 iterations"
+    return res
+
+
 def cpu_baseline(cfg, target_s):
     """The oracle, as it stands, on a bounded row sample of the same workload."""
     import oracle
@@ -390,6 +419,8 @@ def main():
         "step_ms_median": step_ms[len(step_ms) // 2] if step_ms else None, "step_ms_min": step_ms[0] if step_ms else None,
         "limb_roofline_ring_mac_per_s": PEAK_INT8_TOPS * 1e12 / INT8_OPS_PER_RING_MAC,
     }
+    if path == spin.LIMB_MFMA:
+        out["mfma_ceiling"] = mfma_ceiling(roofline["achieved"])
     if not args.no_cpu_baseline:
         del Xs, Ys, Z, T, V, ws
         torch.cuda.empty_cache()

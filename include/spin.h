@@ -227,11 +227,24 @@ typedef enum {
     SPIN_KERNEL_LINCOMB = 8,
     SPIN_KERNEL_BINARY = 9,     /* bshare, bopen, beaver_and */
     SPIN_KERNEL_CAST = 10,      /* spin_cast_64_to_32 */
-    SPIN_KERNEL_COUNT = 11
+    SPIN_KERNEL_PROBE = 11,     /* spin_probe_mfma */
+    SPIN_KERNEL_COUNT = 12
 } spin_kernel;
 void spin_profile_enable(int on);
 spin_status spin_profile_read(spin_kernel kernel, double *total_ms, unsigned *launches);
 void spin_profile_reset(void);
+
+/* Measurement aid: the int8 matrix-core rate the chip sustains on given operand bytes.  Every wave
+ * of `blocks` workgroups (4 waves each) loads 24 MFMA operand fragments of 1 KiB from `operands`
+ * ([24][128] uint64_t: 16 left fragments for two 32x32 tiles, then 8 right fragments; lane l of a wave
+ * reads bytes 16 l .. 16 l + 15 of each) and issues, `iters` times, the 72 v_mfma_i32_32x32x32_i8 of one
+ * k-step of the 64-bit limb GEMM (digit pairs i + j <= 7, pairs of one diagonal sharing an
+ * accumulator), with no memory or LDS access inside the loop: blocks * 4 * iters * 72 * 65536 int8
+ * operations per call.  sink[blocks * 256] receives each thread's wrapped int32 sum of its
+ * accumulator registers, sign-extended (it keeps the loop alive and lets a test check the
+ * arithmetic).  1 <= blocks <= 2^20, 1 <= iters <= 2^20.  Time it with spin_profile_* or events.  */
+spin_status spin_probe_mfma(const uint64_t *operands, int blocks, int iters, uint64_t *sink,
+                            spin_stream stream);
 
 /* Static description of a status code. */
 const char *spin_status_string(spin_status status);

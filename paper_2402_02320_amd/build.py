@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspin.so")
-SOURCES = ["spin_api.hip", "elementwise.hip", "gemm_valu.hip", "gemm_limb.hip", "gemm_limb128.hip"]
+SOURCES = ["spin_api.hip", "elementwise.hip", "gemm_valu.hip", "gemm_limb.hip", "gemm_limb128.hip", "probe.hip"]
 COMPILE_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                  "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                  "-Wall", "-Wno-unused-command-line-argument"]

@@ -103,6 +103,7 @@ size_t limb_workspace_bytes(int n, int batch, int M, int N, int K);
 spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s);
 size_t limb32_workspace_bytes(int n, int batch, int M, int N, int K);
 spin_status launch_matmul_limb32(const MatmulArgs32 &a, hipStream_t s);
+spin_status launch_mfma_probe(const u64 *operands, int blocks, int iters, u64 *sink, hipStream_t s);
 size_t limb128_workspace_bytes(int n, int batch, int M, int N, int K);
 spin_status launch_matmul_limb128(const MatmulArgs128 &a, hipStream_t s);
 

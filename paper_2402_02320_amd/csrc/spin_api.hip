@@ -352,6 +352,13 @@ spin_status spin_cast_64_to_32(const uint64_t *in, size_t count, uint32_t *out, 
     return launch_cast_low(in, count, out, (hipStream_t)stream);
 }
 
+spin_status spin_probe_mfma(const uint64_t *operands, int blocks, int iters, uint64_t *sink, spin_stream stream)
+{
+    if (bad_ptr(operands) || bad_ptr(sink)) return SPIN_EINVAL;
+    if (blocks < 1 || blocks > (1 << 20) || iters < 1 || iters > (1 << 20)) return SPIN_EINVAL;
+    return launch_mfma_probe(operands, blocks, iters, sink, (hipStream_t)stream);
+}
+
 const char *spin_status_string(spin_status status)
 {
     switch (status) {

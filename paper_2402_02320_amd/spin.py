@@ -73,6 +73,8 @@ def lib():
         for name in ("spin32_share", "spin32_open", "spin32_beaver_matmul", "spin32_beaver_mul", "spin32_trunc",
                      "spin_cast_64_to_32"):
             getattr(L, name).restype = i32
+        L.spin_probe_mfma.argtypes = [p, i32, i32, p, p]
+        L.spin_probe_mfma.restype = i32
         L.spin_status_string.argtypes = [i32]
         L.spin_status_string.restype = ctypes.c_char_p
         L.spin_last_hip_error.restype = ctypes.c_char_p
@@ -372,7 +374,20 @@ class ring32:
 
 
 KERNELS = {"random": 0, "share": 1, "open": 2, "beaver_mul": 3, "trunc": 4, "pack": 5, "gemm_limb": 6,
-           "gemm_valu": 7, "lincomb": 8, "binary": 9, "cast": 10}
+           "gemm_valu": 7, "lincomb": 8, "binary": 9, "cast": 10, "probe": 11}
+
+
+def probe_mfma(operands, blocks, iters, sink=None):
+    """Register-only int8 MFMA loop on the 24 operand fragments in `operands` ([24*128] int64); returns sink."""
+    if operands.numel() != 24 * 128:
+        raise SpinError("operands must hold 24 fragments of 128 words")
+    if sink is None:
+        sink = torch.empty(blocks * 256, dtype=torch.int64, device=operands.device)
+    _check(lib().spin_probe_mfma(_dev(operands, "operands"), blocks, iters, _dev(sink, "sink"), _stream()))
+    return sink
+
+
+PROBE_OPS_PER_WAVE_ITERATION = 72 * 65536      # 72 MFMAs of 32x32x32 multiply-adds, two operations each
 
 
 def profile_enable(on=True):
