@@ -86,6 +86,68 @@ def test_int32_accumulators_with_wraparound_recombine_exactly():
         assert total % (1 << 64) == want
 
 
+def wrapped_diagonal_dot(a_vals, b_vals, limbs):
+    """sum_k a_k b_k mod 2^(8 limbs) from int32 accumulators that wrap, one per diagonal."""
+    sa = np.array([digits(int(v), limbs) for v in a_vals], dtype=object)
+    sb = np.array([digits(int(v), limbs) for v in b_vals], dtype=object)
+    total, exact_by_diag = 0, []
+    for d in range(limbs):
+        exact = sum(int(sum(int(x) * int(y) for x, y in zip(sa[:, i], sb[:, d - i]))) for i in range(d + 1))
+        exact_by_diag.append(exact)
+        total += ((exact + (1 << 31)) % (1 << 32) - (1 << 31)) << (8 * d)
+    return total % (1 << (8 * limbs)), exact_by_diag
+
+
+def test_four_digit_ring_never_needs_an_inner_dimension_split():
+    # Z_2^32: 10 pairs, 4 diagonals, each needing at most 32 exact bits, so wrapped accumulators are
+    # right at any length; the all-(-128) operands overflow int32 on diagonals 1..3 here
+    assert sum(1 for i in range(4) for j in range(4) if i + j <= 3) == 10
+    k = 70000
+    a = [0x7F7F7F80] * k
+    got, exact = wrapped_diagonal_dot(a, a, 4)
+    assert all(abs(e) >= (1 << 31) for e in exact[1:])
+    assert got == (k * 0x7F7F7F80 * 0x7F7F7F80) % (1 << 32)
+    rng = np.random.default_rng(4)
+    a, b = rng.integers(0, 1 << 32, size=(2, 3000), dtype=np.uint64)
+    got, _ = wrapped_diagonal_dot(a, b, 4)
+    assert got == sum(int(x) * int(y) for x, y in zip(a, b)) % (1 << 32)
+
+
+def test_sixteen_digit_ring_chunk_limit():
+    # Z_2^128: 136 pairs; diagonals 0..11 must be exact, which 2 * 170 k-tiles of 32 per launch guarantee
+    assert sum(1 for i in range(16) for j in range(16) if i + j <= 15) == 136
+    ktot = 2 * 170 * 32
+    assert 12 * ktot * (1 << 14) < (1 << 31) <= 12 * (2 * 171 * 32) * (1 << 14)
+    worst = int.from_bytes(b"\x80" + b"\x7f" * 15, "little")
+    assert digits(worst, 16) == [-128] * 16
+    a = [worst] * ktot
+    got, exact = wrapped_diagonal_dot(a, a, 16)
+    assert all(-(1 << 31) <= e < (1 << 31) for e in exact[:12])
+    assert got == (ktot * worst * worst) % (1 << 128)
+
+
+def test_missing_library_raises_instead_of_falling_back(monkeypatch, tmp_path):
+    from paper_2402_02320_amd import spin
+    monkeypatch.setattr(spin, "_lib", None)
+    monkeypatch.setattr(spin, "LIB_PATH", str(tmp_path / "libspin.so"))
+    try:
+        spin.lib()
+    except spin.SpinError as e:
+        assert "not found" in str(e)
+    else:
+        raise AssertionError("a missing library must raise")
+
+
+def test_product_code_never_touches_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2402_02320_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for name in files:
+            if name.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, name)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "liboracle" not in text, name
+                assert "spin_oracle" not in text, name
+
+
 def test_config_table_matches_the_benchmark_definition():
     c = workloads.CONFIGS
     assert (c[1].n, c[1].gemms[0].M, c[1].gemms[0].N, c[1].gemms[0].K) == (3, 64, 64, 64)
