@@ -78,8 +78,8 @@ spin_status spin_open(const uint64_t *shares, const uint64_t *mask, size_t count
  * entry: E = sum_i (X_i - A_i), F = sum_i (Y_i - B_i), then
  *     Z_i = C_i + E.B_i + A_i.F   and party 0 adds E.F once.
  * Row-major operands: X, A [n][batch][M][K]; Y, B [n][batch][K][N];
- * C, Z [n][batch][M][N].  Z may alias C.  A transposed right operand
- * (Q.K^T) is passed already transposed.
+ * C, Z [n][batch][M][N].  Z may alias C.  For a right operand that is stored
+ * transposed (Q.K^T) see spin_beaver_matmul_nt.
  * workspace: device scratch of at least
  * spin_beaver_matmul_workspace_bytes(n,batch,M,N,K,path) bytes, 256-byte
  * aligned; its contents are overwritten.  Any K is accepted: the limb path
@@ -89,6 +89,16 @@ spin_status spin_beaver_matmul(int n, int batch, int M, int N, int K,
                                const uint64_t *A, const uint64_t *B, const uint64_t *C,
                                uint64_t *Z, spin_gemm_path path,
                                void *workspace, size_t workspace_bytes, spin_stream stream);
+
+/* The same with the right operands stored transposed, the layout of K in the attention product
+ * Q.K^T (Section 7.4 multiplies such pairs head by head): Yt, Bt are [n][batch][N][K] row-major and
+ * Z = X . Yt^T.  Everything else, including the workspace size, as for spin_beaver_matmul; the
+ * transposition costs no pass over memory (the right-hand fragments are read along rows).       */
+spin_status spin_beaver_matmul_nt(int n, int batch, int M, int N, int K,
+                                  const uint64_t *X, const uint64_t *Yt,
+                                  const uint64_t *A, const uint64_t *Bt, const uint64_t *C,
+                                  uint64_t *Z, spin_gemm_path path,
+                                  void *workspace, size_t workspace_bytes, spin_stream stream);
 
 /* Bytes of workspace spin_beaver_matmul needs; 0 if the arguments are invalid. */
 size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path);

@@ -92,6 +92,7 @@ template <class T> struct MatmulArgsT {
     const T *X, *Y, *A, *B, *C;
     T *Z;
     void *workspace;
+    bool y_transposed;     // Y and B are stored [n][batch][N][K] instead of [n][batch][K][N]
 };
 typedef MatmulArgsT<u64> MatmulArgs;
 typedef MatmulArgsT<u128> MatmulArgs128;

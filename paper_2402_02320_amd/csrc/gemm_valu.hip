@@ -11,7 +11,8 @@ namespace {
 constexpr int TM = 64, TN = 64, TK = 16;   // workgroup tile; 256 threads, 4x4 outputs each
 constexpr int PADA = 2;
 
-template <class T>
+// YT: the right operands F and B_i are stored [N][K] (a transposed right operand, as K in Q.K^T).
+template <class T, bool YT>
 __global__ __launch_bounds__(256) void valu_gemm_kernel(int n, int batch, int M, int N, int K,
                                                        const T *__restrict__ E, const T *__restrict__ F,
                                                        const T *__restrict__ A, const T *__restrict__ B,
@@ -53,8 +54,9 @@ __global__ __launch_bounds__(256) void valu_gemm_kernel(int n, int batch, int M,
                 int gk = k0 + kk, gn = n0 + col + j;
                 T v = 0;
                 if (gk < K && gn < N) {
-                    v = right[(size_t)gk * N + gn];
-                    if (!second && party == 0) v += Fb[(size_t)gk * N + gn];
+                    const size_t e = YT ? (size_t)gn * K + gk : (size_t)gk * N + gn;
+                    v = right[e];
+                    if (!second && party == 0) v += Fb[e];
                 }
                 Bs[kk][col + j] = v;
             }
@@ -112,7 +114,8 @@ template <class T> spin_status launch_matmul_valu(const MatmulArgsT<T> &a, hipSt
     KernelTimer timer(SPIN_KERNEL_GEMM_VALU, s);
     // tiles on the x axis (the y axis holds at most 65535 blocks, fewer than the tile rows of a long operand)
     dim3 grid((unsigned)((size_t)((a.N + TN - 1) / TN) * ((a.M + TM - 1) / TM)), 1, a.n * a.batch);
-    valu_gemm_kernel<T><<<grid, 256, 0, s>>>(a.n, a.batch, a.M, a.N, a.K, E, F, a.A, a.B, a.C, a.Z);
+    if (a.y_transposed) valu_gemm_kernel<T, true><<<grid, 256, 0, s>>>(a.n, a.batch, a.M, a.N, a.K, E, F, a.A, a.B, a.C, a.Z);
+    else valu_gemm_kernel<T, false><<<grid, 256, 0, s>>>(a.n, a.batch, a.M, a.N, a.K, E, F, a.A, a.B, a.C, a.Z);
     return check_launch("spin_beaver_matmul(valu)");
 }
 template spin_status launch_matmul_valu<u32>(const MatmulArgsT<u32> &, hipStream_t);

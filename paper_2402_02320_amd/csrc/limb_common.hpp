@@ -160,7 +160,10 @@ __global__ __launch_bounds__(256) void pack_right_kernel(PackArgs<T> a)
 // shares in that layout, and turns each 32 x 32 tile through LDS (rows padded by 16 bytes,
 // conflict-free for 16-byte accesses both ways) so that each lane ends up with the 16 consecutive k
 // of one row that a fragment chunk needs.  WAVES = waves per block (LDS: WAVES x 32 padded rows).
-template <int NP, class T, bool VEC, int WAVES>
+// RIGHT = true packs a right operand that is stored transposed ([N][K] row-major, the layout of K in
+// Q.K^T): the access pattern is the left side's, the slot rule the right side's (party 0's slot holds
+// B_0 + F).
+template <int NP, class T, bool VEC, int WAVES, bool RIGHT>
 __global__ __launch_bounds__(64 * WAVES) void pack_left_kernel(PackArgs<T> a)
 {
     constexpr int ND = sizeof(T);
@@ -260,12 +263,24 @@ __global__ __launch_bounds__(64 * WAVES) void pack_left_kernel(PackArgs<T> a)
     }
     turn_and_store(opened, frag(0));
     if constexpr (KEEP) {
+        if (RIGHT) {
+#pragma unroll
+            for (int j = 0; j < NL; ++j)
+#pragma unroll
+                for (int q = 0; q < EPL; ++q) first[j].e[q] += opened[j].e[q];
+        }
         turn_and_store(first, frag(1));
     } else {
         Pair tv[NL];
         const T *t = a.tri + (size_t)b * mat;
 #pragma unroll
-        for (int j = 0; j < NL; ++j) tv[j] = load(t, blk * 32 + RPL * j + lane / LPR);
+        for (int j = 0; j < NL; ++j) {
+            tv[j] = load(t, blk * 32 + RPL * j + lane / LPR);
+            if (RIGHT) {
+#pragma unroll
+                for (int q = 0; q < EPL; ++q) tv[j].e[q] += opened[j].e[q];
+            }
+        }
         turn_and_store(tv, frag(1));
     }
 }
@@ -313,17 +328,25 @@ template <class T>
 inline void launch_pack(const MatmulArgsT<T> &a, char *packA, char *packB, int nblkA, int nblkB, int KT, hipStream_t s)
 {
     PackArgs<T> pa{a.X, a.A, packA, a.n, a.batch, a.M, a.K, nblkA, KT};
-    PackArgs<T> pb{a.Y, a.B, packB, a.n, a.batch, a.K, a.N, nblkB, KT};
     constexpr int WAVES = sizeof(T) <= 8 ? 4 : 2;
     constexpr int EPL = 16 / sizeof(T);
+    const bool vec = a.K % EPL == 0;                     // rows 16-byte aligned
     for_party_count(a.n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
         KernelTimer timer(SPIN_KERNEL_PACK, s);
         dim3 ga((unsigned)(((long)nblkA * KT + WAVES - 1) / WAVES), 1, a.batch);
-        if (a.K % EPL == 0) pack_left_kernel<NP, T, true, WAVES><<<ga, 64 * WAVES, 0, s>>>(pa);   // rows 16-byte aligned
-        else pack_left_kernel<NP, T, false, WAVES><<<ga, 64 * WAVES, 0, s>>>(pa);
-        dim3 gb((unsigned)(((long)((nblkB + 1) / 2) * KT * 2 + 3) / 4), 1, a.batch);
-        pack_right_kernel<NP, T><<<gb, 256, 0, s>>>(pb);
+        if (vec) pack_left_kernel<NP, T, true, WAVES, false><<<ga, 64 * WAVES, 0, s>>>(pa);
+        else pack_left_kernel<NP, T, false, WAVES, false><<<ga, 64 * WAVES, 0, s>>>(pa);
+        if (a.y_transposed) {                            // Y, B stored [N][K]: rows of the source are fragment rows
+            PackArgs<T> pb{a.Y, a.B, packB, a.n, a.batch, a.N, a.K, nblkB, KT};
+            dim3 gb((unsigned)(((long)nblkB * KT + WAVES - 1) / WAVES), 1, a.batch);
+            if (vec) pack_left_kernel<NP, T, true, WAVES, true><<<gb, 64 * WAVES, 0, s>>>(pb);
+            else pack_left_kernel<NP, T, false, WAVES, true><<<gb, 64 * WAVES, 0, s>>>(pb);
+        } else {
+            PackArgs<T> pb{a.Y, a.B, packB, a.n, a.batch, a.K, a.N, nblkB, KT};
+            dim3 gb((unsigned)(((long)((nblkB + 1) / 2) * KT * 2 + 3) / 4), 1, a.batch);
+            pack_right_kernel<NP, T><<<gb, 256, 0, s>>>(pb);
+        }
     });
 }
 

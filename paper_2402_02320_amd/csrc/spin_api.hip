@@ -107,9 +107,10 @@ size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K,
     return 0;
 }
 
-spin_status spin_beaver_matmul(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Y,
-                               const uint64_t *A, const uint64_t *B, const uint64_t *C, uint64_t *Z,
-                               spin_gemm_path path, void *workspace, size_t workspace_bytes, spin_stream stream)
+static spin_status beaver_matmul64(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Y,
+                                   const uint64_t *A, const uint64_t *B, const uint64_t *C, uint64_t *Z,
+                                   spin_gemm_path path, void *workspace, size_t workspace_bytes, spin_stream stream,
+                                   bool y_transposed)
 {
     if (bad_ptr(X) || bad_ptr(Y) || bad_ptr(A) || bad_ptr(B) || bad_ptr(C) || bad_ptr(Z)) return SPIN_EINVAL;
     if (path != SPIN_GEMM_LIMB_MFMA && path != SPIN_GEMM_VALU) return SPIN_EINVAL;
@@ -118,9 +119,23 @@ spin_status spin_beaver_matmul(int n, int batch, int M, int N, int K, const uint
     const size_t need = spin_beaver_matmul_workspace_bytes(n, batch, M, N, K, path);
     if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need)
         return SPIN_EWORKSPACE;
-    MatmulArgs a{n, batch, M, N, K, X, Y, A, B, C, Z, workspace};
+    MatmulArgs a{n, batch, M, N, K, X, Y, A, B, C, Z, workspace, y_transposed};
     return path == SPIN_GEMM_LIMB_MFMA ? launch_matmul_limb(a, (hipStream_t)stream)
                                        : launch_matmul_valu(a, (hipStream_t)stream);
+}
+
+spin_status spin_beaver_matmul(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Y,
+                               const uint64_t *A, const uint64_t *B, const uint64_t *C, uint64_t *Z,
+                               spin_gemm_path path, void *workspace, size_t workspace_bytes, spin_stream stream)
+{
+    return beaver_matmul64(n, batch, M, N, K, X, Y, A, B, C, Z, path, workspace, workspace_bytes, stream, false);
+}
+
+spin_status spin_beaver_matmul_nt(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Yt,
+                                  const uint64_t *A, const uint64_t *Bt, const uint64_t *C, uint64_t *Z,
+                                  spin_gemm_path path, void *workspace, size_t workspace_bytes, spin_stream stream)
+{
+    return beaver_matmul64(n, batch, M, N, K, X, Yt, A, Bt, C, Z, path, workspace, workspace_bytes, stream, true);
 }
 
 spin_status spin_beaver_mul(int n, size_t count, const uint64_t *x, const uint64_t *y, const uint64_t *a,
@@ -258,7 +273,7 @@ spin_status spin128_beaver_matmul(int n, int batch, int M, int N, int K, const u
     const size_t need = spin128_beaver_matmul_workspace_bytes(n, batch, M, N, K, path);
     if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need)
         return SPIN_EWORKSPACE;
-    MatmulArgs128 a{n, batch, M, N, K, r128(X), r128(Y), r128(A), r128(B), r128(C), r128(Z), workspace};
+    MatmulArgs128 a{n, batch, M, N, K, r128(X), r128(Y), r128(A), r128(B), r128(C), r128(Z), workspace, false};
     return path == SPIN_GEMM_LIMB_MFMA ? launch_matmul_limb128(a, (hipStream_t)stream)
                                        : launch_matmul_valu<u128>(a, (hipStream_t)stream);
 }
@@ -321,7 +336,7 @@ spin_status spin32_beaver_matmul(int n, int batch, int M, int N, int K, const ui
     const size_t need = spin32_beaver_matmul_workspace_bytes(n, batch, M, N, K, path);
     if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need)
         return SPIN_EWORKSPACE;
-    MatmulArgs32 a{n, batch, M, N, K, X, Y, A, B, C, Z, workspace};
+    MatmulArgs32 a{n, batch, M, N, K, X, Y, A, B, C, Z, workspace, false};
     return path == SPIN_GEMM_LIMB_MFMA ? launch_matmul_limb32(a, (hipStream_t)stream)
                                        : launch_matmul_valu<u32>(a, (hipStream_t)stream);
 }

@@ -35,6 +35,8 @@ def lib():
         L.spin_share.argtypes = [p, sz, i32, u64, u64, p, p]
         L.spin_open.argtypes = [p, p, sz, i32, p, p]
         L.spin_beaver_matmul.argtypes = [i32] * 5 + [p] * 6 + [i32, p, sz, p]
+        L.spin_beaver_matmul_nt.argtypes = L.spin_beaver_matmul.argtypes
+        L.spin_beaver_matmul_nt.restype = i32
         L.spin_beaver_matmul_workspace_bytes.argtypes = [i32] * 5 + [i32]
         L.spin_beaver_matmul_workspace_bytes.restype = sz
         L.spin_beaver_mul.argtypes = [i32, sz] + [p] * 6 + [p]
@@ -129,12 +131,13 @@ def beaver_matmul_workspace_bytes(n, batch, M, N, K, path=LIMB_MFMA):
     return int(lib().spin_beaver_matmul_workspace_bytes(n, batch, M, N, K, path))
 
 
-def beaver_matmul(X, Y, A, B, C, path=LIMB_MFMA, out=None, workspace=None):
-    """X, A: [n,batch,M,K]; Y, B: [n,batch,K,N]; C: [n,batch,M,N] -> Z [n,batch,M,N]."""
+def beaver_matmul(X, Y, A, B, C, path=LIMB_MFMA, out=None, workspace=None, y_transposed=False):
+    """X, A: [n,batch,M,K]; Y, B: [n,batch,K,N] (or [n,batch,N,K] with y_transposed, for X . Y^T);
+    C: [n,batch,M,N] -> Z [n,batch,M,N]."""
     n, batch, M, K = X.shape
-    N = Y.shape[3]
-    if tuple(Y.shape) != (n, batch, K, N) or A.shape != X.shape or B.shape != Y.shape \
-            or tuple(C.shape) != (n, batch, M, N):
+    N = Y.shape[2] if y_transposed else Y.shape[3]
+    yshape = (n, batch, N, K) if y_transposed else (n, batch, K, N)
+    if tuple(Y.shape) != yshape or A.shape != X.shape or B.shape != Y.shape or tuple(C.shape) != (n, batch, M, N):
         raise SpinError("inconsistent operand shapes")
     if out is None:
         out = torch.empty_like(C)
@@ -145,9 +148,9 @@ def beaver_matmul(X, Y, A, B, C, path=LIMB_MFMA, out=None, workspace=None):
         workspace = torch.empty(need, dtype=torch.uint8, device=X.device)
     if not (workspace.is_cuda and workspace.is_contiguous()):
         raise SpinError("workspace must be a contiguous CUDA tensor")
-    _check(lib().spin_beaver_matmul(n, batch, M, N, K, _dev(X, "X"), _dev(Y, "Y"), _dev(A, "A"), _dev(B, "B"),
-                                    _dev(C, "C"), _dev(out, "Z"), path, workspace.data_ptr(),
-                                    workspace.numel() * workspace.element_size(), _stream()))
+    call = lib().spin_beaver_matmul_nt if y_transposed else lib().spin_beaver_matmul
+    _check(call(n, batch, M, N, K, _dev(X, "X"), _dev(Y, "Y"), _dev(A, "A"), _dev(B, "B"), _dev(C, "C"),
+                _dev(out, "Z"), path, workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
     return out
 
 

@@ -61,6 +61,9 @@ def test_argument_validation_needs_no_gpu(L):
     assert mm(2, 1, 4, 4, 4, fake, fake, fake, fake, fake, fake, 0, None, 0, None) == EWORKSPACE
     assert mm(2, 1, 4, 4, 4, fake, fake, fake, fake, fake, fake, 0, fake, 16, None) == EWORKSPACE
     assert mm(2, 1, 1 << 25, 4, 4, fake, fake, fake, fake, fake, fake, 0, fake, 1 << 30, None) == ERANGE
+    nt = L.spin_beaver_matmul_nt
+    assert nt(2, 1, 4, 4, 4, fake, None, fake, fake, fake, fake, 0, fake, 1 << 30, None) == EINVAL
+    assert nt(2, 1, 4, 4, 4, fake, fake, fake, fake, fake, fake, 1, fake, 16, None) == EWORKSPACE
 
 
 def test_workspace_query(L):

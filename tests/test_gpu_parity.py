@@ -143,6 +143,21 @@ def test_beaver_matmul_in_place_on_c(path):
 
 
 @pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("n,batch,M,N,K", [(1, 1, 1, 1, 1), (2, 1, 33, 31, 32), (3, 2, 130, 70, 45), (5, 1, 129, 65, 33),
+                                           (3, 64, 128, 128, 64), (2, 1, 300, 260, 257), (4, 3, 17, 200, 101)])
+def test_beaver_matmul_with_transposed_right_operand(n, batch, M, N, K, path):
+    # Y and B handed over as [n][batch][N][K] (the layout of K in Q.K^T); same result as the plain call
+    rng = np.random.default_rng(n * 31 + M)
+    X, Y = rand_u64(rng, (n, batch, M, K)), rand_u64(rng, (n, batch, K, N))
+    A, B, C = oracle.dealer_matmul(n, batch, M, N, K, seed=n * 31 + M)
+    want = oracle.beaver_matmul(X, Y, A, B, C)
+    Yt = np.ascontiguousarray(Y.transpose(0, 1, 3, 2))
+    Bt = np.ascontiguousarray(B.transpose(0, 1, 3, 2))
+    got = spin.beaver_matmul(dev(X), dev(Yt), dev(A), dev(Bt), dev(C), path=path, y_transposed=True)
+    assert (host(got) == want).all()
+
+
+@pytest.mark.parametrize("path", PATHS)
 def test_tall_operand_with_more_tile_rows_than_a_grid_axis_holds(path):
     # 65537 tile rows of 64 (VALU path) exceed the 65535 blocks of a grid's y and z axes
     M = 65536 * 64 + 1
