@@ -2,12 +2,16 @@
  * spin.h -- C ABI of the MI355X (gfx950) library for the per-party local work
  * of additive-secret-sharing multiplication over the ring Z_2^64:
  * sharing, opening, the Beaver-triple share update for matrix and elementwise
- * products, and fixed-point truncation.
+ * products, and fixed-point truncation (spin_share, spin_open,
+ * spin_beaver_matmul, spin_beaver_mul, spin_trunc).  Further down: the same
+ * over Z_2^32 and Z_2^128 (spin32_*, spin128_*), binary shares (spin_b*),
+ * a public linear combination with fused truncation, and measurement aids.
  *
  * Conventions that hold for every entry point
  * -------------------------------------------
- *  - Ring elements are uint64_t; all arithmetic wraps mod 2^64.  Read as signed
- *    they are the range [-2^63, 2^63-1] of Section 4.1 (Notations).
+ *  - Ring elements are uint64_t unless a section says otherwise; all arithmetic
+ *    wraps mod 2^64.  Read as signed they are the range [-2^63, 2^63-1] of
+ *    Section 4.1 (Notations).
  *  - All n parties live on the one GPU.  Share tensors are party-major:
  *    T[i] is party i's share, contiguous, so a tensor of `count` elements is
  *    laid out [n][count].  Party 0 is the paper's party 1: it holds residual
