@@ -208,6 +208,41 @@ def beaver_mul(x, y, a, b, c, l=64):
     return z
 
 
+def tile_factor(x, outer, mid, inner, over_inner):
+    """Section 7.3: before the batch multiplication E * R the smaller array is tiled up to the size of the
+    other one ("the notation E * R implies this tiling").  x: [n][outer][mid] (over_inner, one factor per row)
+    or [n][outer][inner] (one factor per column) -> [n][outer*mid*inner]."""
+    x = _u64(x)
+    n = x.shape[0]
+    if over_inner:
+        t = np.broadcast_to(x.reshape(n, outer, mid, 1), (n, outer, mid, inner))
+    else:
+        t = np.broadcast_to(x.reshape(n, outer, 1, inner), (n, outer, mid, inner))
+    return np.ascontiguousarray(t).reshape(n, -1)
+
+
+def dealer_mul_bcast(n, outer, mid, inner, over_inner, seed, l=64):
+    """Triple for the tiled multiplication: a has the shape of the small factor and is tiled like it,
+    b is full-sized, c shares (tiled a) * b."""
+    small = outer * (mid if over_inner else inner)
+    full = outer * mid * inner
+    a = np.stack([random(small, seed, STREAM_A, i) for i in range(n)])
+    b = np.stack([random(full, seed, STREAM_B, i) for i in range(n)])
+    if l < 64:
+        a &= np.uint64((1 << l) - 1)
+        b &= np.uint64((1 << l) - 1)
+    prod = open_(tile_factor(a, outer, mid, inner, over_inner), l=l) * open_(b, l=l)      # uint64 arithmetic wraps
+    if l < 64:
+        prod &= np.uint64((1 << l) - 1)
+    return a, b, share(prod, n, seed, STREAM_C, l=l)
+
+
+def beaver_mul_bcast(x, y, a, b, c, outer, mid, inner, over_inner, l=64):
+    """The batch multiplication with one factor tiled (Section 7.3), by its definition: tile, then Mul."""
+    return beaver_mul(tile_factor(x, outer, mid, inner, over_inner), y,
+                      tile_factor(a, outer, mid, inner, over_inner), b, c, l=l)
+
+
 def trunc_dealer(n, count, f, seed, l=64):
     r = np.empty((n, count), dtype=np.uint64)
     rt = np.empty((n, count), dtype=np.uint64)

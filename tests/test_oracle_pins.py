@@ -361,3 +361,37 @@ def test_decoded_truncated_product_matches_float64(n, dist):
     assert np.abs(got - x[0] @ y[0]).max() <= 2.0 ** -f * (K + 2)
     # before truncation the product is exact at precision 2f
     assert np.abs(oracle.decode(oracle.open_(Z), 2 * f)[0] - xq[0] @ yq[0]).max() < 1e-9
+
+
+# ----------------------------------------------------------------------------- tiled batch multiplication (Section 7.3)
+def test_tiled_multiplication_reconstructs_and_matches_python_integers():
+    rng = np.random.default_rng(73)
+    for over_inner in (True, False):
+        n, outer, mid, inner = 3, 2, 5, 4
+        small = outer * (mid if over_inner else inner)
+        x = rng.integers(0, 1 << 64, size=small, dtype=np.uint64)
+        y = rng.integers(0, 1 << 64, size=outer * mid * inner, dtype=np.uint64)
+        X, Y = oracle.share(x, n, 1, oracle.STREAM_X), oracle.share(y, n, 1, oracle.STREAM_Y)
+        a, b, c = oracle.dealer_mul_bcast(n, outer, mid, inner, over_inner, seed=2)
+        # the triple: c opens to (tiled a) * b, in Python integers
+        ao, bo, co = oracle.open_(a), oracle.open_(b), oracle.open_(c)
+        z = oracle.open_(oracle.beaver_mul_bcast(X, Y, a, b, c, outer, mid, inner, over_inner))
+        for o in range(outer):
+            for m in range(mid):
+                for i in range(inner):
+                    k = (o * mid + m) * inner + i
+                    s = o * mid + m if over_inner else o * inner + i
+                    assert int(co[k]) == int(ao[s]) * int(bo[k]) % (1 << 64)
+                    assert int(z[k]) == int(x[s]) * int(y[k]) % (1 << 64)
+
+
+def test_tiling_a_factor_of_full_size_is_the_plain_multiplication():
+    # inner = 1 (rows) or mid = 1 (columns): nothing is repeated, and the result is Mul itself
+    rng = np.random.default_rng(74)
+    n, count = 2, 50
+    X, Y = rng.integers(0, 1 << 64, size=(2, n, count), dtype=np.uint64)
+    a, b, c = oracle.dealer_mul(n, count, seed=3)
+    want = oracle.beaver_mul(X, Y, a, b, c)
+    assert (oracle.beaver_mul_bcast(X, Y, a, b, c, count, 1, 1, True) == want).all()
+    assert (oracle.beaver_mul_bcast(X, Y, a, b, c, 1, 1, count, False) == want).all()
+    assert (oracle.beaver_mul_bcast(X, Y, a, b, c, 5, 10, 1, True) == want).all()
