@@ -117,6 +117,19 @@ spin_status spin_beaver_mul(int n, size_t count,
                             const uint64_t *a, const uint64_t *b, const uint64_t *c,
                             uint64_t *z, spin_stream stream);
 
+/* The same with one factor tiled, the batch multiplication E * R of Section 7.3 in which the smaller
+ * array is repeated along one axis up to the size of the other (and its downsized form R * V).  The
+ * large operands y, b, c and the result z are [n][outer][mid][inner]; the small factor x and its mask a
+ * are [n][outer][mid] when over_inner != 0 (one factor per row, repeated along inner) and
+ * [n][outer][inner] when over_inner == 0 (one factor per column, repeated along mid).  With xt, at the
+ * tiled arrays, z equals spin_beaver_mul(n, outer*mid*inner, xt, y, at, b, c); the triple satisfies
+ * sum_i c_i = (tiled sum_i a_i) * (sum_i b_i).  The tiled arrays are never formed: 4n instead of 6n
+ * words move per element.  z may alias y, b or c.                                                   */
+spin_status spin_beaver_mul_bcast(int n, size_t outer, size_t mid, size_t inner, int over_inner,
+                                  const uint64_t *x, const uint64_t *y,
+                                  const uint64_t *a, const uint64_t *b, const uint64_t *c,
+                                  uint64_t *z, spin_stream stream);
+
 /* Signed probabilistic truncation by f bits (Section 4.4 Truncation):
  * Truncate(x,f) = UnsignedTruncate(x + 2^62, 64, f) - 2^(62-f), correct up to
  * one unit for x in [-2^62, 2^62-1] and undefined (not an error) outside.

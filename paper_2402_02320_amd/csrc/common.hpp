@@ -72,6 +72,8 @@ template <class T> spin_status launch_open(const T *shares, const T *mask, size_
 template <class T>
 spin_status launch_beaver_mul(int n, size_t count, const T *x, const T *y, const T *a, const T *b, const T *c, T *z,
                               hipStream_t s);
+spin_status launch_beaver_mul_bcast(int n, size_t outer, size_t mid, size_t inner, bool over_inner, const u64 *x,
+                                    const u64 *y, const u64 *a, const u64 *b, const u64 *c, u64 *z, hipStream_t s);
 template <class T>
 spin_status launch_trunc(int n, size_t count, int f, const T *x, const T *r, const T *r_top, const T *r_msb, T *out,
                          hipStream_t s);

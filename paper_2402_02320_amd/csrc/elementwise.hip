@@ -142,6 +142,37 @@ __global__ __launch_bounds__(kBlock) void beaver_mul_kernel(const T *x, const T 
     }
 }
 
+// The same update with one factor tiled (Section 7.3: E * R with R repeated along an axis): x and a hold
+// one element per (outer, mid) row (OVER_INNER) or per (outer, inner) column of the [outer][mid][inner]
+// tensors y, b, c, z.  The tiled array is never materialised: every thread reads its factor's 2n words
+// from the small arrays (cache hits after the first touch) and streams 4n words of the large ones.
+template <int NP, bool OVER_INNER, bool NT>
+__global__ __launch_bounds__(kBlock) void beaver_mul_bcast_kernel(const u64 *__restrict__ x, const u64 *y,
+                                                                 const u64 *__restrict__ a, const u64 *b,
+                                                                 const u64 *c, size_t small_count, size_t count,
+                                                                 size_t mid, size_t inner, u64 *z)
+{
+    size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= count) return;
+    const size_t sidx = OVER_INNER ? v / inner : v / (mid * inner) * inner + v % inner;
+    u64 xv[NP], yv[NP], av[NP], bv[NP], cv[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        size_t o = (size_t)i * count + v, so = (size_t)i * small_count + sidx;
+        xv[i] = x[so]; av[i] = a[so];
+        yv[i] = ld<NT>(y + o); bv[i] = ld<NT>(b + o); cv[i] = ld<NT>(c + o);
+    }
+    u64 e = 0, f = 0;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) { e += xv[i] - av[i]; f += yv[i] - bv[i]; }
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        u64 bi = bv[i];
+        if (i == 0) bi += f;
+        st<NT>(z + (size_t)i * count + v, cv[i] + e * bi + av[i] * f);
+    }
+}
+
 // The combine of the signed probabilistic truncation (Section 4.4) on party shares y[] held in
 // registers; steps as listed at spin_trunc in include/spin.h.
 template <int NP, class T, bool NT>
@@ -372,6 +403,27 @@ spin_status launch_beaver_mul(int n, size_t count, const T *x, const T *y, const
         });
     });
     return check_launch("spin_beaver_mul");
+}
+
+spin_status launch_beaver_mul_bcast(int n, size_t outer, size_t mid, size_t inner, bool over_inner, const u64 *x,
+                                    const u64 *y, const u64 *a, const u64 *b, const u64 *c, u64 *z, hipStream_t s)
+{
+    const size_t count = outer * mid * inner, small_count = outer * (over_inner ? mid : inner);
+    if (small_count == count) return launch_beaver_mul<u64>(n, count, x, y, a, b, c, z, s);   // nothing is repeated
+    KernelTimer timer(SPIN_KERNEL_BEAVER_MUL, s);
+    for_party_count(n, [&](auto np) {
+        constexpr int NP = decltype(np)::value;
+        for_streaming((size_t)n * count * sizeof(u64), [&](auto nt) {
+            constexpr bool NT = decltype(nt)::value;
+            if (over_inner)
+                beaver_mul_bcast_kernel<NP, true, NT><<<grid_for(count), kBlock, 0, s>>>(x, y, a, b, c, small_count,
+                                                                                        count, mid, inner, z);
+            else
+                beaver_mul_bcast_kernel<NP, false, NT><<<grid_for(count), kBlock, 0, s>>>(x, y, a, b, c, small_count,
+                                                                                         count, mid, inner, z);
+        });
+    });
+    return check_launch("spin_beaver_mul_bcast");
 }
 
 template <class T>

@@ -40,6 +40,8 @@ def lib():
         L.spin_beaver_matmul_workspace_bytes.argtypes = [i32] * 5 + [i32]
         L.spin_beaver_matmul_workspace_bytes.restype = sz
         L.spin_beaver_mul.argtypes = [i32, sz] + [p] * 6 + [p]
+        L.spin_beaver_mul_bcast.argtypes = [i32, sz, sz, sz, i32] + [p] * 6 + [p]
+        L.spin_beaver_mul_bcast.restype = i32
         L.spin_trunc.argtypes = [i32, sz, i32] + [p] * 5 + [p]
         L.spin_lincomb_trunc.argtypes = [i32, sz, i32, p, p, u64, i32, p, p, p, p, p]
         L.spin_lincomb_trunc.restype = i32
@@ -163,6 +165,20 @@ def beaver_mul(x, y, a, b, c, out=None):
         out = torch.empty_like(x)
     _check(lib().spin_beaver_mul(n, x[0].numel(), _dev(x, "x"), _dev(y, "y"), _dev(a, "a"), _dev(b, "b"),
                                  _dev(c, "c"), _dev(out, "z"), _stream()))
+    return out
+
+
+def beaver_mul_bcast(x, y, a, b, c, over_inner, out=None):
+    """Batch multiplication with the small factor tiled (Section 7.3).  y, b, c: [n, outer, mid, inner];
+    x, a: [n, outer, mid] (over_inner, one factor per row) or [n, outer, inner] (one per column)."""
+    n, outer, mid, inner = y.shape
+    small = (n, outer, mid) if over_inner else (n, outer, inner)
+    if tuple(x.shape) != small or a.shape != x.shape or b.shape != y.shape or c.shape != y.shape:
+        raise SpinError("inconsistent operand shapes")
+    if out is None:
+        out = torch.empty_like(y)
+    _check(lib().spin_beaver_mul_bcast(n, outer, mid, inner, 1 if over_inner else 0, _dev(x, "x"), _dev(y, "y"),
+                                       _dev(a, "a"), _dev(b, "b"), _dev(c, "c"), _dev(out, "z"), _stream()))
     return out
 
 

@@ -123,3 +123,13 @@ def test_validation_of_the_32_bit_entry_points(L):
     # limb path: n+1 digit-fragment copies of the operands padded to 128 x 128 tiles, 4 bytes per element
     assert q(2, 1, 1024, 1024, 1024, 0) == 4 * 3 * (1024 * 1024 * 2)
     assert q(2, 1, 100, 100, 100, 0) == 4 * 3 * (128 * 128 * 2)
+
+
+def test_validation_of_the_tiled_multiplication(L):
+    fake = ctypes.c_void_p(0x1000)
+    EINVAL, ERANGE = 1, 2
+    f = L.spin_beaver_mul_bcast
+    assert f(2, 0, 4, 4, 1, fake, fake, fake, fake, fake, fake, None) == EINVAL
+    assert f(2, 4, 4, 4, 1, fake, fake, None, fake, fake, fake, None) == EINVAL
+    assert f(9, 4, 4, 4, 0, fake, fake, fake, fake, fake, fake, None) == EINVAL
+    assert f(2, 1 << 20, 1 << 20, 4, 0, fake, fake, fake, fake, fake, fake, None) == ERANGE

@@ -93,3 +93,60 @@ def test_downsized_batch_multiplication(n, heads, D1, D3, path):
     assert np.abs(oracle.decode(oracle.open_(lhs), 3 * f) - want).max() <= 2.0 ** -f * (D2 + 2) * 2
     # and the sizes the paper quotes: the elementwise product shrinks by D1 / D3
     assert so[0].size // wo[0].size == D1 // D3
+
+
+@pytest.mark.parametrize("n,outer,mid,inner", [(1, 1, 1, 1), (2, 1, 7, 1), (3, 2, 5, 33), (5, 4, 196, 64), (2, 3, 100, 257),
+                                               (8, 1, 3, 1000)])
+@pytest.mark.parametrize("over_inner", [True, False])
+def test_tiled_factor_multiplication_matches_the_oracle(n, outer, mid, inner, over_inner):
+    rng = np.random.default_rng(n * 100 + mid + inner)
+    small = outer * (mid if over_inner else inner)
+    x = rng.integers(0, 1 << 64, size=small, dtype=np.uint64)
+    y = rng.integers(0, 1 << 64, size=outer * mid * inner, dtype=np.uint64)
+    X, Y = oracle.share(x, n, 5, oracle.STREAM_X), oracle.share(y, n, 5, oracle.STREAM_Y)
+    a, b, c = oracle.dealer_mul_bcast(n, outer, mid, inner, over_inner, seed=6)
+    want = oracle.beaver_mul_bcast(X, Y, a, b, c, outer, mid, inner, over_inner)
+    full = (n, outer, mid, inner)
+    sshape = (n, outer, mid) if over_inner else (n, outer, inner)
+    yd = dev(Y.reshape(full))
+    got = spin.beaver_mul_bcast(dev(X.reshape(sshape)), yd, dev(a.reshape(sshape)), dev(b.reshape(full)),
+                                dev(c.reshape(full)), over_inner)
+    assert (host(got).reshape(n, -1) == want).all()
+    # in place on the large operand
+    spin.beaver_mul_bcast(dev(X.reshape(sshape)), yd, dev(a.reshape(sshape)), dev(b.reshape(full)),
+                          dev(c.reshape(full)), over_inner, out=yd)
+    assert (host(yd).reshape(n, -1) == want).all()
+
+
+def test_tiled_factor_multiplication_at_streaming_size():
+    n, outer, mid, inner = 3, 8, 512, 1024                      # 3 x 4 Mi words: past the non-temporal threshold
+    rng = np.random.default_rng(9)
+    for over_inner in (True, False):
+        small = outer * (mid if over_inner else inner)
+        x = rng.integers(0, 1 << 64, size=small, dtype=np.uint64)
+        y = rng.integers(0, 1 << 64, size=outer * mid * inner, dtype=np.uint64)
+        X, Y = oracle.share(x, n, 5, oracle.STREAM_X), oracle.share(y, n, 5, oracle.STREAM_Y)
+        a, b, c = oracle.dealer_mul_bcast(n, outer, mid, inner, over_inner, seed=6)
+        want = oracle.beaver_mul_bcast(X, Y, a, b, c, outer, mid, inner, over_inner)
+        full = (n, outer, mid, inner)
+        sshape = (n, outer, mid) if over_inner else (n, outer, inner)
+        got = spin.beaver_mul_bcast(dev(X.reshape(sshape)), dev(Y.reshape(full)), dev(a.reshape(sshape)),
+                                    dev(b.reshape(full)), dev(c.reshape(full)), over_inner)
+        assert (host(got).reshape(n, -1) == want).all()
+
+
+def test_downsized_order_with_the_factor_tiled_inside_the_kernel():
+    # E @ (R * V) with R [1 x D2] handed over untiled: R scales the rows of V
+    n, heads, D2, D3, f = 3, 4, 196, 64, 14
+    rng = np.random.default_rng(11)
+    Rr = rng.uniform(0.001, 0.05, size=(heads, D2))
+    V = rng.normal(0, 1, size=(heads, D2, D3))
+    Rs, Vs = shared(Rr, n, f, 21, 1), shared(V, n, f, 21, 2)
+    a, b, c = oracle.dealer_mul_bcast(n, heads, D2, D3, True, seed=22)
+    wo = oracle.beaver_mul_bcast(Rs.reshape(n, -1), Vs.reshape(n, -1), a, b, c, heads, D2, D3, True)
+    wd = spin.beaver_mul_bcast(dev(Rs), dev(Vs), dev(a.reshape(n, heads, D2)), dev(b.reshape(Vs.shape)),
+                               dev(c.reshape(Vs.shape)), True)
+    assert (host(wd).reshape(n, -1) == wo).all()
+    wtd, wto = trunc_both(wd.view(n, -1), wo, n, f, 23)
+    got = oracle.decode(host(spin.open(wtd)), f).reshape(V.shape)
+    assert np.abs(got - Rr[:, :, None] * V).max() <= 2.0 ** -f * 3 * max(1.0, np.abs(V).max())
