@@ -318,6 +318,27 @@ def test_paths_agree_on_config5_shape_slice():
     assert torch.equal(z0, z1)
 
 
+@pytest.mark.parametrize("n", [4, 6, 7, 8])
+def test_every_party_count_at_a_multi_tile_size(n):
+    # 512 x 384 x 640: several workgroup tiles and 20 k-tiles per operand pair; both paths against each other,
+    # sampled rows against the oracle, and the truncated result through the fused open
+    M, N, K, f = 512, 384, 640, 16
+    rng = np.random.default_rng(80 + n)
+    X, Y = rand_u64(rng, (n, 1, M, K)), rand_u64(rng, (n, 1, K, N))
+    A, B, C = oracle.dealer_matmul(n, 1, M, N, K, seed=80 + n)
+    args = [dev(t) for t in (X, Y, A, B, C)]
+    zl = spin.beaver_matmul(*args, path=spin.LIMB_MFMA)
+    zv = spin.beaver_matmul(*args, path=spin.VALU)
+    assert torch.equal(zl, zv)
+    rows = np.sort(rng.choice(M, 48, replace=False)); rows[0], rows[-1] = 0, M - 1
+    assert (host(zl)[:, :, rows] == oracle.beaver_matmul(X, Y, A, B, C, rows=rows)).all()
+    r, rt, rm = oracle.trunc_dealer(n, M * N, f, seed=81 + n)
+    got = host(spin.trunc(zl.view(n, -1), dev(r), dev(rt), dev(rm), f)).reshape(n, M, N)[:, rows]
+    idx = (np.asarray(rows)[:, None] * N + np.arange(N)).reshape(-1)
+    want = oracle.trunc(host(zl).reshape(n, -1)[:, idx], r[:, idx], rt[:, idx], rm[:, idx], f)
+    assert (got.reshape(n, -1) == want).all()
+
+
 def test_calls_run_on_the_callers_stream():
     # the whole path enqueued on a side stream, with no synchronisation until the end: every call must be
     # ordered on that stream (a kernel launched on another stream would read unfinished inputs)
