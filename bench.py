@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time its replays (for the launch-bound small "
                          "configurations; the per-kernel figures then come from a separate eager pass)")
+    ap.add_argument("--fuse-mul-trunc", action="store_true",
+                    help="run the elementwise multiplication and its truncation as the one-pass spin_beaver_mul_trunc")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
@@ -319,8 +321,11 @@ def main():
         spin.share(y, n, c.seed, S["Y"], out=Ys)
         spin.beaver_matmul(Xs, Ys, A, B, C, path=path, out=Z, workspace=ws)
         spin.trunc(Z.view(n, -1), r1[0], r1[1], r1[2], f, out=T)
-        spin.beaver_mul(T, w, ea, eb, ec, out=V)
-        spin.trunc(V, r2[0], r2[1], r2[2], f, out=V)
+        if args.fuse_mul_trunc:
+            spin.beaver_mul_trunc(T, w, ea, eb, ec, r2[0], r2[1], r2[2], f, out=V)
+        else:
+            spin.beaver_mul(T, w, ea, eb, ec, out=V)
+            spin.trunc(V, r2[0], r2[1], r2[2], f, out=V)
 
     # one plain copy of known size (open of a single share: out[k] = shares[0][k]); the HBM byte counters
     # of a profiler run are calibrated against what they read for this launch (1 GiB in, 1 GiB out)
@@ -399,7 +404,8 @@ def main():
     el = 8.0 * szC
     streams = {}
     per_call_bytes = {"share": (1 + n) * 8.0 * (szA + szB) / 2, "trunc": 5 * n * el, "beaver_mul": 6 * n * el,
-                      "pack": 8.0 * ((2 * n + n + 1) * szA + (2 * n + n + 1) * szB)}
+                      "pack": 8.0 * ((2 * n + n + 1) * szA + (2 * n + n + 1) * szB),
+                      "beaver_mul_trunc": 9 * n * el}
     for k, b in per_call_bytes.items():
         ms, cnt = kernels[k]
         if cnt:
@@ -414,7 +420,8 @@ def main():
         "config": {"workload": "config %d: %d parties, batch %d, M=%d N=%d K=%d, f=%d, %s; step = share X,Y + Beaver "
                                "matmul (open+update) + trunc + elementwise Beaver mul + trunc" %
                                (args.config, n, batch, M, N, K, f, c.dist),
-                   "gemm_path": args.path, "parties": n, "launch": "hip graph replay" if args.graph else "eager"},
+                   "gemm_path": args.path, "parties": n, "launch": "hip graph replay" if args.graph else "eager",
+                   "mul_trunc": "one pass" if args.fuse_mul_trunc else "two calls"},
         "roofline": roofline, "stream_kernels": streams,
         "step_ms_median": step_ms[len(step_ms) // 2] if step_ms else None, "step_ms_min": step_ms[0] if step_ms else None,
         "limb_roofline_ring_mac_per_s": PEAK_INT8_TOPS * 1e12 / INT8_OPS_PER_RING_MAC,

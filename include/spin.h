@@ -144,6 +144,17 @@ spin_status spin_trunc(int n, size_t count, int f, const uint64_t *x,
                        const uint64_t *r, const uint64_t *r_top, const uint64_t *r_msb,
                        uint64_t *out, spin_stream stream);
 
+/* Fixed-point multiplication in one pass: spin_beaver_mul followed by spin_trunc of its result
+ * (a product carries twice the precision, Section 4.3; Truncate brings it back, Section 4.4), with
+ * the product shares kept in registers instead of written and read again.  out equals
+ * spin_trunc(n, count, f, z, r, r_top, r_msb) of z = spin_beaver_mul(n, count, x, y, a, b, c) word
+ * for word.  Shapes and aliasing as for those two calls; out may alias any input.  1 <= f <= 61. */
+spin_status spin_beaver_mul_trunc(int n, size_t count, int f,
+                                  const uint64_t *x, const uint64_t *y,
+                                  const uint64_t *a, const uint64_t *b, const uint64_t *c,
+                                  const uint64_t *r, const uint64_t *r_top, const uint64_t *r_msb,
+                                  uint64_t *out, spin_stream stream);
+
 /* Public-coefficient linear combination followed by one truncation: the local
  * part of Scale and Add (Section 4.3) and the single deferred truncation of
  * polynomial evaluation (Section 4.4, Polynomial evaluation; the fused
@@ -255,7 +266,8 @@ typedef enum {
     SPIN_KERNEL_BINARY = 9,     /* bshare, bopen, beaver_and */
     SPIN_KERNEL_CAST = 10,      /* spin_cast_64_to_32 */
     SPIN_KERNEL_PROBE = 11,     /* spin_probe_mfma */
-    SPIN_KERNEL_COUNT = 12
+    SPIN_KERNEL_MUL_TRUNC = 12, /* spin_beaver_mul_trunc */
+    SPIN_KERNEL_COUNT = 13
 } spin_kernel;
 void spin_profile_enable(int on);
 spin_status spin_profile_read(spin_kernel kernel, double *total_ms, unsigned *launches);

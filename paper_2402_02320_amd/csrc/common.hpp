@@ -72,6 +72,9 @@ template <class T> spin_status launch_open(const T *shares, const T *mask, size_
 template <class T>
 spin_status launch_beaver_mul(int n, size_t count, const T *x, const T *y, const T *a, const T *b, const T *c, T *z,
                               hipStream_t s);
+spin_status launch_beaver_mul_trunc(int n, size_t count, int f, const u64 *x, const u64 *y, const u64 *a, const u64 *b,
+                                    const u64 *c, const u64 *r, const u64 *r_top, const u64 *r_msb, u64 *out,
+                                    hipStream_t s);
 spin_status launch_beaver_mul_bcast(int n, size_t outer, size_t mid, size_t inner, bool over_inner, const u64 *x,
                                     const u64 *y, const u64 *a, const u64 *b, const u64 *c, u64 *z, hipStream_t s);
 template <class T>

@@ -147,6 +147,18 @@ spin_status spin_beaver_mul(int n, size_t count, const uint64_t *x, const uint64
     return launch_beaver_mul(n, count, x, y, a, b, c, z, (hipStream_t)stream);
 }
 
+spin_status spin_beaver_mul_trunc(int n, size_t count, int f, const uint64_t *x, const uint64_t *y, const uint64_t *a,
+                                  const uint64_t *b, const uint64_t *c, const uint64_t *r, const uint64_t *r_top,
+                                  const uint64_t *r_msb, uint64_t *out, spin_stream stream)
+{
+    if (bad_ptr(x) || bad_ptr(y) || bad_ptr(a) || bad_ptr(b) || bad_ptr(c) || bad_ptr(r) || bad_ptr(r_top) ||
+        bad_ptr(r_msb) || bad_ptr(out) || bad_n(n) || count == 0)
+        return SPIN_EINVAL;
+    if (f < 1 || f > 61) return SPIN_EINVAL;
+    if (count > kMaxCount) return SPIN_ERANGE;
+    return launch_beaver_mul_trunc(n, count, f, x, y, a, b, c, r, r_top, r_msb, out, (hipStream_t)stream);
+}
+
 spin_status spin_beaver_mul_bcast(int n, size_t outer, size_t mid, size_t inner, int over_inner, const uint64_t *x,
                                   const uint64_t *y, const uint64_t *a, const uint64_t *b, const uint64_t *c,
                                   uint64_t *z, spin_stream stream)

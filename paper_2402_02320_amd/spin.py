@@ -40,6 +40,8 @@ def lib():
         L.spin_beaver_matmul_workspace_bytes.argtypes = [i32] * 5 + [i32]
         L.spin_beaver_matmul_workspace_bytes.restype = sz
         L.spin_beaver_mul.argtypes = [i32, sz] + [p] * 6 + [p]
+        L.spin_beaver_mul_trunc.argtypes = [i32, sz, i32] + [p] * 9 + [p]
+        L.spin_beaver_mul_trunc.restype = i32
         L.spin_beaver_mul_bcast.argtypes = [i32, sz, sz, sz, i32] + [p] * 6 + [p]
         L.spin_beaver_mul_bcast.restype = i32
         L.spin_trunc.argtypes = [i32, sz, i32] + [p] * 5 + [p]
@@ -165,6 +167,20 @@ def beaver_mul(x, y, a, b, c, out=None):
         out = torch.empty_like(x)
     _check(lib().spin_beaver_mul(n, x[0].numel(), _dev(x, "x"), _dev(y, "y"), _dev(a, "a"), _dev(b, "b"),
                                  _dev(c, "c"), _dev(out, "z"), _stream()))
+    return out
+
+
+def beaver_mul_trunc(x, y, a, b, c, r, r_top, r_msb, f, out=None):
+    """Mul then Truncate by f bits in one pass; all operands [n, count]."""
+    n = x.shape[0]
+    for t in (y, a, b, c, r, r_top, r_msb):
+        if t.shape != x.shape:
+            raise SpinError("inconsistent operand shapes")
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib().spin_beaver_mul_trunc(n, x[0].numel(), f, _dev(x, "x"), _dev(y, "y"), _dev(a, "a"), _dev(b, "b"),
+                                       _dev(c, "c"), _dev(r, "r"), _dev(r_top, "r_top"), _dev(r_msb, "r_msb"),
+                                       _dev(out, "out"), _stream()))
     return out
 
 
@@ -393,7 +409,7 @@ class ring32:
 
 
 KERNELS = {"random": 0, "share": 1, "open": 2, "beaver_mul": 3, "trunc": 4, "pack": 5, "gemm_limb": 6,
-           "gemm_valu": 7, "lincomb": 8, "binary": 9, "cast": 10, "probe": 11}
+           "gemm_valu": 7, "lincomb": 8, "binary": 9, "cast": 10, "probe": 11, "beaver_mul_trunc": 12}
 
 
 def probe_mfma(operands, blocks, iters, sink=None):

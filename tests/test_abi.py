@@ -133,3 +133,13 @@ def test_validation_of_the_tiled_multiplication(L):
     assert f(2, 4, 4, 4, 1, fake, fake, None, fake, fake, fake, None) == EINVAL
     assert f(9, 4, 4, 4, 0, fake, fake, fake, fake, fake, fake, None) == EINVAL
     assert f(2, 1 << 20, 1 << 20, 4, 0, fake, fake, fake, fake, fake, fake, None) == ERANGE
+
+
+def test_validation_of_the_fused_multiplication(L):
+    fake = ctypes.c_void_p(0x1000)
+    EINVAL = 1
+    f = L.spin_beaver_mul_trunc
+    assert f(2, 8, 0, fake, fake, fake, fake, fake, fake, fake, fake, fake, None) == EINVAL
+    assert f(2, 8, 62, fake, fake, fake, fake, fake, fake, fake, fake, fake, None) == EINVAL
+    assert f(2, 8, 16, fake, fake, fake, fake, fake, fake, None, fake, fake, None) == EINVAL
+    assert f(2, 0, 16, fake, fake, fake, fake, fake, fake, fake, fake, fake, None) == EINVAL

@@ -77,6 +77,30 @@ def test_trunc(n, f, count):
     assert (host(Xd) == want).all()
 
 
+@pytest.mark.parametrize("n,f", [(1, 16), (2, 16), (3, 14), (5, 16), (8, 20)])
+@pytest.mark.parametrize("count", [1, 2, 777, 70001, (1 << 21) + 2])
+def test_beaver_mul_trunc_is_mul_then_trunc(n, f, count):
+    if n * count * 8 >= 64 << 20 and n not in (5, 8):
+        pytest.skip("the streaming variant is covered at n = 5 and 8")
+    rng = np.random.default_rng(n * 7 + count)
+    xs = rng.integers(-(1 << 28), 1 << 28, size=count, dtype=np.int64).view(np.uint64)
+    ys = rng.integers(-(1 << 28), 1 << 28, size=count, dtype=np.int64).view(np.uint64)
+    X, Y = oracle.share(xs, n, 31, oracle.STREAM_X), oracle.share(ys, n, 31, oracle.STREAM_Y)
+    a, b, c = oracle.dealer_mul(n, count, seed=32)
+    r, rt, rm = oracle.trunc_dealer(n, count, f, seed=33)
+    want = oracle.trunc(oracle.beaver_mul(X, Y, a, b, c), r, rt, rm, f)
+    Xd = dev(X)
+    args = (dev(Y), dev(a), dev(b), dev(c), dev(r), dev(rt), dev(rm), f)
+    got = spin.beaver_mul_trunc(Xd, *args)
+    assert (host(got) == want).all()
+    # the opened result is the product shifted down, up to the truncation's one unit (first 1000 elements)
+    opened = host(spin.open(got)).view(np.int64)[:1000]
+    floors = [(int(p) * int(q)) >> f for p, q in zip(xs.view(np.int64)[:1000], ys.view(np.int64)[:1000])]
+    assert set(int(o) - w for o, w in zip(opened, floors)) <= {0, 1}
+    spin.beaver_mul_trunc(Xd, *args, out=Xd)                     # in place on the first operand
+    assert (host(Xd) == want).all()
+
+
 # Past 64 MB per call the many-stream kernels switch to non-temporal loads and stores; both the paired
 # (even count) and the single-word (odd count) forms of that variant are compared here.
 @pytest.mark.parametrize("n,count", [(5, (1 << 21) + 2), (3, (3 << 20) + 1), (8, 1 << 20)])
