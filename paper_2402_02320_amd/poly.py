@@ -24,8 +24,7 @@ def evaluate_poly(x, coeffs, p, triples, tuples):
     powers = [x]
     for i in range(2, d + 1):
         a, b, c = triples[i - 2]
-        prod = spin.beaver_mul(powers[-1], x, a, b, c)
-        powers.append(spin.trunc(prod, *tuples[i - 2], p, out=prod))
+        powers.append(spin.beaver_mul_trunc(powers[-1], x, a, b, c, *tuples[i - 2], p))   # Mul + Truncate, one pass
     return spin.lincomb_trunc(powers, [encode_public(coeffs[i], p) for i in range(1, d + 1)],
                               encode_public(coeffs[0], 2 * p), p, tuples[-1])
 
@@ -37,8 +36,7 @@ def evaluate_completed_square(x, k4p_log2, t3, t2, t1, t0, p, triples, tuples):
     shift = -k4p_log2
     k4p = 2.0 ** k4p_log2
     u = spin.lincomb_trunc([x], [1], encode_public(t3, p))
-    u2 = spin.beaver_mul(u, u, *triples[0])
-    spin.trunc(u2, *tuples[0], p, out=u2)
+    u2 = spin.beaver_mul_trunc(u, u, *triples[0], *tuples[0], p)
     v = spin.lincomb_trunc([u2], [1], encode_public(t2, p), out=u2)
     v2 = spin.beaver_mul(v, v, *triples[1])
     return spin.lincomb_trunc([v2, x], [1, encode_public(k4p * t1, p) << shift],
