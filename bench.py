@@ -129,7 +129,15 @@ def cpu_baseline(cfg, target_s):
     t_a, t_b = run(r1), run(2 * r1)
     oracle.set_threads(threads)
     one_core = 2 * c.n * batch * r1 * N * K / max(t_b - t_a, 1e-9)
-    return {"value": credited / t, "unit": "ring MAC/s", "cores": threads, "kind": "oracle",
+    model = ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return {"value": credited / t, "unit": "ring MAC/s", "cores": threads, "cpu_model": model, "kind": "oracle",
             "sample": "config %d, %d of %d output rows of every party's share (%.1f s, incl. opening E and F; "
                       "%.3g ring MACs executed, %.3g credited as n*2*rows*N*K)" % (cfg, nrows, M, t, macs, credited),
             "one_core_value": one_core,
@@ -425,6 +433,8 @@ def main():
         "roofline": roofline, "stream_kernels": streams,
         "step_ms_median": step_ms[len(step_ms) // 2] if step_ms else None, "step_ms_min": step_ms[0] if step_ms else None,
         "limb_roofline_ring_mac_per_s": PEAK_INT8_TOPS * 1e12 / INT8_OPS_PER_RING_MAC,
+        # the protocol's view: one secure product of the plaintext shapes per step, whatever n
+        "secure_matmul_mac_per_s": batch * M * N * K / (ms_per_step * 1e-3),
     }
     if path == spin.LIMB_MFMA:
         out["mfma_ceiling"] = mfma_ceiling(roofline["achieved"])
