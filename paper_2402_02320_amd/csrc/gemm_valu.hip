@@ -42,9 +42,11 @@ __global__ __launch_bounds__(256) void valu_gemm_kernel(int n, int batch, int M,
         {   // left tile: 64 rows x 16 k, 4 elements per thread, stored transposed
             int row = threadIdx.x / 4, kk = (threadIdx.x % 4) * 4;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < 4; ++j) {                // unconditional loads: out of range reads element 0, then zero
                 int gm = m0 + row, gk = k0 + kk + j;
-                As[kk + j][row] = (gm < M && gk < K) ? left[(size_t)gm * K + gk] : 0;
+                const bool ok = gm < M && gk < K;
+                const T v = left[ok ? (size_t)gm * K + gk : 0];
+                As[kk + j][row] = ok ? v : (T)0;
             }
         }
         {   // right tile: 16 k x 64 cols
@@ -52,13 +54,11 @@ __global__ __launch_bounds__(256) void valu_gemm_kernel(int n, int batch, int M,
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 int gk = k0 + kk, gn = n0 + col + j;
-                T v = 0;
-                if (gk < K && gn < N) {
-                    const size_t e = YT ? (size_t)gn * K + gk : (size_t)gk * N + gn;
-                    v = right[e];
-                    if (!second && party == 0) v += Fb[e];
-                }
-                Bs[kk][col + j] = v;
+                const bool ok = gk < K && gn < N;
+                const size_t e = !ok ? 0 : YT ? (size_t)gn * K + gk : (size_t)gk * N + gn;
+                T v = right[e];
+                if (!second && party == 0) v += Fb[e];
+                Bs[kk][col + j] = ok ? v : (T)0;
             }
         }
         __syncthreads();
