@@ -252,7 +252,8 @@ spin_status spin_cast_64_to_32(const uint64_t *in, size_t count, uint32_t *out, 
  * (this is the one place the library allocates, and only while enabled).
  * spin_profile_read waits for the recorded events, and returns the summed
  * duration in milliseconds and the number of launches of one kernel class
- * since the last spin_profile_reset.  Not thread-safe.                        */
+ * since the last spin_profile_reset.  Not thread-safe; leave it disabled while a
+ * stream is being captured into a HIP graph (recorded events cannot be timed). */
 typedef enum {
     SPIN_KERNEL_RANDOM = 0,
     SPIN_KERNEL_SHARE = 1,
