@@ -66,6 +66,8 @@ template <class T> struct GemmArgs {
     int nblkA, nblkB, KT;
     int kt0, ktn;        // this launch covers k-tiles [kt0, kt0+ktn) of both operand pairs
     int tilesM, tilesN;
+    int splits;          // workgroups per output tile: each takes split_steps of the 2*ktn k-steps and, when
+    int split_steps;     // splits > 1, adds its part onto Z atomically (Z then starts out as C)
 };
 
 template <class T>
@@ -82,6 +84,9 @@ struct GemmShape {
     static constexpr int mfma_per_step = ND * (ND + 1) / 2 * WM * WN;
     static_assert(ND * WM * WN * 16 <= 256, "accumulators exceed the AGPR file");
 };
+
+__device__ inline void ring_atomic_add(u64 *p, u64 v) { atomicAdd((unsigned long long *)p, (unsigned long long)v); }
+__device__ inline void ring_atomic_add(u32 *p, u32 v) { atomicAdd((unsigned int *)p, (unsigned int)v); }
 
 // Pipeline (per wave; step s covers one 32-deep k-tile of one operand pair; counts for Z_2^64):
 //   G(s)  12 direct-to-LDS loads of this wave's share of step s into LDS stage s % 3
@@ -101,7 +106,11 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
     const int wm = wave / 2, wn = wave % 2;
 
-    const TileId tile = map_tile(blockIdx.x, g.tilesM, g.tilesN, (long)g.tilesM * g.tilesN * g.n * g.batch);
+    // work item = (split, tile), tiles fastest: neighbours on an XCD work on neighbouring tiles of one k-range
+    const long tiles_total = (long)g.tilesM * g.tilesN * g.n * g.batch;
+    const long item = xcd_contiguous_id(blockIdx.x, tiles_total * g.splits);
+    const int split = (int)(item / tiles_total);
+    const TileId tile = tile_of(item % tiles_total, g.tilesM, g.tilesN);
     const int pb = tile.pb, tm = tile.tm, tn = tile.tn;
     const int party = pb / g.batch, b = pb % g.batch;
 
@@ -113,7 +122,10 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
     const char *b_second = g.packB + (size_t)b * g.nblkB * g.KT * (kDigits * kFrag);  // F
     const char *b_first = b_second + (size_t)(1 + party) * slotB;                      // B_i'
 
-    const int steps = 2 * g.ktn;
+    // this workgroup's k-steps [s0, s0 + steps) of the 2 * ktn (both counts even)
+    const int s0 = split * g.split_steps;
+    const int steps = min(g.split_steps, 2 * g.ktn - s0);
+    const bool starts_in_second = s0 >= g.ktn;
     const u32 lds0 = (u32)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
     const u32 lane16 = lane * 16;
 
@@ -124,11 +136,12 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
     // of the tile and digit f % ND = 4 (q % (ND/4)) + wave, so only q-dependent constants remain per load.
     const size_t blk_stride = (size_t)g.KT * (kDigits * kFrag);
     const size_t kt0_off = (size_t)g.kt0 * (kDigits * kFrag) + wave * kFrag;
-    const char *ld_a = a_first + (size_t)tm * (S::BM / 32) * blk_stride + kt0_off;
-    const char *ld_b = b_first + (size_t)tn * (S::BN / 32) * blk_stride + kt0_off;
     const char *second_a = a_second + (size_t)tm * (S::BM / 32) * blk_stride + kt0_off;
     const char *second_b = b_second + (size_t)tn * (S::BN / 32) * blk_stride + kt0_off;
-    int ld_left = g.ktn;                                 // steps until the cursor switches operand pair
+    const size_t start_off = (size_t)(starts_in_second ? s0 - g.ktn : s0) * (kDigits * kFrag);
+    const char *ld_a = (starts_in_second ? second_a : a_first + (size_t)tm * (S::BM / 32) * blk_stride + kt0_off) + start_off;
+    const char *ld_b = (starts_in_second ? second_b : b_first + (size_t)tn * (S::BN / 32) * blk_stride + kt0_off) + start_off;
+    int ld_left = starts_in_second ? 0x7fffffff : g.ktn - s0;   // steps until the cursor switches operand pair
     u32 ld_lds = lds0 + wave * kFrag;                    // LDS destination of the cursor's stage
     const u32 lds_wrap = lds0 + wave * kFrag + (S::NSTAGE - 1) * S::stage_bytes;
     auto issue_load = [&](int q) {                       // q is a compile-time constant after unrolling
@@ -270,6 +283,9 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
     const T *Cm = g.C + (size_t)pb * mat;
     T *Zm = g.Z + (size_t)pb * mat;
     const bool interior = (tm + 1) * S::BM <= g.M && (tn + 1) * S::BN <= g.N;     // uniform over the workgroup
+    // With several workgroups per tile (splits > 1) Z already holds C and every part is added atomically:
+    // ring addition is associative and commutative, so the result does not depend on the order of arrival.
+    const bool atomic = g.splits > 1;
 #pragma unroll
     for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -279,7 +295,10 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
             auto row_of = [&](int r) { return row0 + 8 * (r / 4) + r % 4; };
             T v[16];
             __builtin_amdgcn_sched_barrier(0);           // keeps the scheduler from hoisting the next tile's work
-            if (interior) {
+            if (atomic) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) v[r] = 0;
+            } else if (interior) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) v[r] = Cm[(size_t)row_of(r) * g.N + col];
             } else {
@@ -292,7 +311,11 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
             for (int r = 0; r < 16; ++r)
 #pragma unroll
                 for (int d = 0; d < kDigits; ++d) v[r] += (T)(int64_t)acc[i][j][d][r] << (8 * d);
-            if (interior) {
+            if (atomic) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (interior || (row_of(r) < g.M && col < g.N)) ring_atomic_add(Zm + (size_t)row_of(r) * g.N + col, v[r]);
+            } else if (interior) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) Zm[(size_t)row_of(r) * g.N + col] = v[r];
             } else {
@@ -322,6 +345,35 @@ template <class T> inline Plan make_plan(int n, int batch, int M, int N, int K)
     return p;
 }
 
+// How many workgroups share one output tile.  One workgroup per CU is resident at a time, so `tiles`
+// tiles of `steps` k-steps take ceil(tiles / CUs) rounds of steps + a fixed prologue/epilogue cost; when
+// the tiles do not fill the chip, splitting the k-steps of each tile over several workgroups (which add
+// their parts onto Z atomically) shortens the rounds.  Returns the count that minimises that model.
+inline int choose_splits(long tiles, int steps)
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            cus = v;
+        else
+            cus = 256;
+    }
+    constexpr int kFixedCost = 8;                        // prologue + epilogue, in k-step equivalents
+    constexpr int kMinSteps = 8;                         // shorter parts are all overhead
+    long best_cost = -1;
+    int best = 1;
+    for (int sp = 1; sp <= 16; ++sp) {
+        const int part = 2 * ceil_div(ceil_div(steps, 2), sp);
+        if (sp > 1 && part < kMinSteps) break;
+        const long rounds = (tiles * sp + cus - 1) / cus;
+        const long cost = rounds * (part + kFixedCost);
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = sp; }
+    }
+    return best;
+}
+
 template <class T> spin_status launch_limb(const MatmulArgsT<T> &a, hipStream_t s, const char *where_pack, const char *where_gemm)
 {
     using S = GemmShape<T>;
@@ -341,15 +393,27 @@ template <class T> spin_status launch_limb(const MatmulArgsT<T> &a, hipStream_t 
         if (e != hipSuccess) { note_hip_error(e, "hipFuncSetAttribute"); return SPIN_EHIP; }
         attr_set = true;
     }
-    GemmArgs<T> g{packA, packB, a.C, a.Z, a.n, a.batch, a.M, a.N, p.nblkA, p.nblkB, p.KT, 0, 0, p.tilesM, p.tilesN};
+    GemmArgs<T> g{packA, packB, a.C, a.Z, a.n, a.batch, a.M, a.N, p.nblkA, p.nblkB, p.KT, 0, 0, p.tilesM, p.tilesN,
+                  1, 0};
     const long total = (long)p.tilesM * p.tilesN * a.n * a.batch;
     constexpr int chunk = Ring<T>::max_chunk_tiles;
+    const int first_ktn = p.KT < chunk ? p.KT : chunk;
+    const int splits = choose_splits(total, 2 * first_ktn);
+    if (splits > 1 && a.C != a.Z) {                      // the parts are added onto Z, which starts out as C
+        st = launch_open<T>(a.C, nullptr, (size_t)a.n * a.batch * a.M * a.N, 1, a.Z, s);
+        if (st != SPIN_OK) return st;
+    }
     for (int kt0 = 0; kt0 < p.KT; kt0 += chunk) {
         g.kt0 = kt0;
         g.ktn = p.KT - kt0 < chunk ? p.KT - kt0 : chunk;
         g.C = kt0 == 0 ? a.C : a.Z;                      // later chunks accumulate onto Z
+        g.splits = splits;
+        g.split_steps = 2 * ceil_div(g.ktn, splits);     // even, so that every part has an even number of steps
+        const int used = ceil_div(2 * g.ktn, g.split_steps);     // parts that actually have steps
+        g.splits = used;
+        if (splits > 1 && used == 1) g.C = a.Z;          // a short last chunk in one part: plain accumulate onto Z
         KernelTimer timer(SPIN_KERNEL_GEMM_LIMB, s);
-        kernel<<<(unsigned)total, 256, S::lds_bytes, s>>>(g);
+        kernel<<<(unsigned)(total * used), 256, S::lds_bytes, s>>>(g);
     }
     return check_launch(where_gemm);
 }

@@ -298,16 +298,19 @@ __device__ inline void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "mem
 __device__ inline void workgroup_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 // Output tile of a workgroup.  Workgroup ids are dealt round-robin to the 8 XCDs; each XCD gets a
-// contiguous range of tiles, so that workgroups sharing an L2 also share operand fragments, and walks
-// it in 4-tile-tall column strips.
-struct TileId { int pb, tm, tn; };     // party * batch + b, tile row, tile column
-__device__ inline TileId map_tile(long id, int tilesM, int tilesN, long total)
+// contiguous range of the work items, so that workgroups sharing an L2 also share operand fragments,
+// and walks the tiles of a matrix in 4-tile-tall column strips.
+__device__ inline long xcd_contiguous_id(long id, long total)
 {
     const long chunk = (total + 7) / 8;
-    const long full = total - (chunk - 1) * 8;       // XCDs that own `chunk` tiles (the rest own chunk-1)
+    const long full = total - (chunk - 1) * 8;       // XCDs that own `chunk` items (the rest own chunk-1)
     const int xcd = (int)(id % 8);
     const long within = id / 8;
-    id = xcd < full ? xcd * chunk + within : full * chunk + (xcd - full) * (chunk - 1) + within;
+    return xcd < full ? xcd * chunk + within : full * chunk + (xcd - full) * (chunk - 1) + within;
+}
+struct TileId { int pb, tm, tn; };     // party * batch + b, tile row, tile column
+__device__ inline TileId tile_of(long id, int tilesM, int tilesN)
+{
     const int per_mat = tilesM * tilesN;
     TileId r;
     r.pb = (int)(id / per_mat);
@@ -319,6 +322,10 @@ __device__ inline TileId map_tile(long id, int tilesM, int tilesN, long total)
     r.tm = strip * GROUP + t % strip_h;
     r.tn = t / strip_h;
     return r;
+}
+__device__ inline TileId map_tile(long id, int tilesM, int tilesN, long total)
+{
+    return tile_of(xcd_contiguous_id(id, total), tilesM, tilesN);
 }
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }

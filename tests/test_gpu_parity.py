@@ -189,6 +189,27 @@ def test_tall_operand_with_more_tile_rows_than_a_grid_axis_holds(path):
     assert (got == want).all()
 
 
+@pytest.mark.parametrize("n,batch,M,N,K", [(2, 1, 128, 64, 4096), (3, 1, 200, 130, 1000), (1, 2, 64, 64, 999),
+                                           (5, 1, 256, 192, 352), (2, 1, 100, 60, 16352 + 320)])
+def test_few_tiles_and_a_long_inner_dimension(n, batch, M, N, K):
+    # fewer output tiles than the chip has CUs: several workgroups share a tile, each taking a run of k-steps
+    # (runs that start in the first operand pair, straddle the switch, or lie in the second) and adding its
+    # part onto Z atomically; out of place (Z first becomes C) and in place on C
+    rng = np.random.default_rng(M + K)
+    X, Y = rand_u64(rng, (n, batch, M, K)), rand_u64(rng, (n, batch, K, N))
+    A, B, C = oracle.dealer_matmul(n, batch, M, N, K, seed=M + K)
+    want = oracle.beaver_matmul(X, Y, A, B, C)
+    Xd, Yd, Ad, Bd, Cd = (dev(t) for t in (X, Y, A, B, C))
+    got = spin.beaver_matmul(Xd, Yd, Ad, Bd, Cd, path=spin.LIMB_MFMA)
+    assert (host(got) == want).all()
+    assert (host(Cd) == C).all()                                  # C untouched
+    spin.beaver_matmul(Xd, Yd, Ad, Bd, Cd, path=spin.LIMB_MFMA, out=Cd)
+    assert (host(Cd) == want).all()
+    # repeated calls give the same words (the atomic accumulation is exact, so order cannot matter)
+    again = spin.beaver_matmul(Xd, Yd, Ad, Bd, dev(C), path=spin.LIMB_MFMA)
+    assert torch.equal(again, got)
+
+
 def test_limb_path_worst_case_digits_and_inner_dimension_split():
     # every digit of every operand equal to -128 (value 0x7F7F7F7F7F7F7F80), with K large enough that
     # the inner dimension is split into more than one accumulation chunk: the int32 partial sums run
