@@ -26,13 +26,25 @@ constexpr int kBlock = 256;
 constexpr size_t kStreamingBytes = (size_t)64 << 20;    // per call, all parties together
 template <bool NT, class V> __device__ inline V ld(const V *p)
 {
-    if constexpr (NT && !std::is_same<V, u128>::value) return __builtin_nontemporal_load(p);
-    else return *p;
+    if constexpr (NT && std::is_same<V, u128>::value) {          // the builtin takes no __int128: same 16 bytes as u64x2
+        const u64x2 w = __builtin_nontemporal_load((const u64x2 *)p);
+        return (u128)w.x | ((u128)w.y << 64);
+    } else if constexpr (NT) {
+        return __builtin_nontemporal_load(p);
+    } else {
+        return *p;
+    }
 }
 template <bool NT, class V> __device__ inline void st(V *p, V v)
 {
-    if constexpr (NT && !std::is_same<V, u128>::value) __builtin_nontemporal_store(v, p);
-    else *p = v;
+    if constexpr (NT && std::is_same<V, u128>::value) {
+        u64x2 w; w.x = (u64)v; w.y = (u64)(v >> 64);
+        __builtin_nontemporal_store(w, (u64x2 *)p);
+    } else if constexpr (NT) {
+        __builtin_nontemporal_store(v, p);
+    } else {
+        *p = v;
+    }
 }
 
 // Lane types.  V = u64x2 (two ring elements per lane) or u64 (odd counts, whose party rows are only

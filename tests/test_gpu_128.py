@@ -90,3 +90,20 @@ def test_matmul_1024_cube_two_parties(path):
     want = r128.beaver_matmul(X[:, :, rows], Y, A[:, :, rows], B, C[:, :, rows])      # rows of Z depend on rows of X, A, C only
     got = R.beaver_matmul(dev(X), dev(Y), dev(A), dev(B), dev(C), path=path)
     assert (host(got)[:, :, rows] == want).all()
+
+
+def test_streaming_sizes():
+    # past 64 MB per call the elementwise kernels use their non-temporal variants
+    n, count, f = 3, (1 << 21) + 1, 40
+    rng = np.random.default_rng(128)
+    x, y = rand_ring(rng, (count,)), rand_ring(rng, (count,))
+    xs, ys = r128.share(x, n, 7, 1), r128.share(y, n, 7, 2)
+    xd = R.share(dev(x), n, 7, 1)
+    assert (host(xd) == xs).all()
+    a, b, c = r128.dealer_mul(n, count, seed=7)
+    assert (host(R.open(xd, dev(a))) == r128.open_(xs, a)).all()
+    want = r128.beaver_mul(xs, ys, a, b, c)
+    zd = R.beaver_mul(xd, dev(ys), dev(a), dev(b), dev(c))
+    assert (host(zd) == want).all()
+    r, rt, rm = r128.trunc_dealer(n, count, f, seed=9)
+    assert (host(R.trunc(zd, dev(r), dev(rt), dev(rm), f)) == r128.trunc(want, r, rt, rm, f)).all()
