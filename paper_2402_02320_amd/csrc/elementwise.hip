@@ -320,7 +320,7 @@ __global__ __launch_bounds__(kBlock) void bshare_kernel(const u64 *__restrict__ 
     shares[v] = rest;
 }
 
-template <int NP, bool MASK>
+template <int NP, bool MASK, bool NT>
 __global__ __launch_bounds__(kBlock) void bopen_kernel(const u64 *__restrict__ shares, const u64 *__restrict__ mask,
                                                       size_t count, u64 *__restrict__ out)
 {
@@ -329,16 +329,16 @@ __global__ __launch_bounds__(kBlock) void bopen_kernel(const u64 *__restrict__ s
     u64 s[NP], m[NP];
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
-        s[i] = shares[(size_t)i * count + v];
-        if (MASK) m[i] = mask[(size_t)i * count + v];
+        s[i] = ld<NT>(shares + (size_t)i * count + v);
+        if (MASK) m[i] = ld<NT>(mask + (size_t)i * count + v);
     }
     u64 acc = 0;
 #pragma unroll
     for (int i = 0; i < NP; ++i) acc ^= MASK ? s[i] ^ m[i] : s[i];
-    out[v] = acc;
+    st<NT>(out + v, acc);
 }
 
-template <int NP>
+template <int NP, bool NT>
 __global__ __launch_bounds__(kBlock) void beaver_and_kernel(const u64 *x, const u64 *y, const u64 *a, const u64 *b,
                                                            const u64 *c, size_t count, u64 *z)
 {
@@ -348,7 +348,8 @@ __global__ __launch_bounds__(kBlock) void beaver_and_kernel(const u64 *x, const 
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
         size_t o = (size_t)i * count + v;
-        xv[i] = x[o]; yv[i] = y[o]; av[i] = a[o]; bv[i] = b[o]; cv[i] = c[o];
+        xv[i] = ld<NT>(x + o); yv[i] = ld<NT>(y + o); av[i] = ld<NT>(a + o); bv[i] = ld<NT>(b + o);
+        cv[i] = ld<NT>(c + o);
     }
     u64 e = 0, f = 0;
 #pragma unroll
@@ -357,7 +358,7 @@ __global__ __launch_bounds__(kBlock) void beaver_and_kernel(const u64 *x, const 
     for (int i = 0; i < NP; ++i) {
         u64 bi = bv[i];
         if (i == 0) bi ^= f;                       // (e & b_0) ^ (e & f) = e & (b_0 ^ f)
-        z[(size_t)i * count + v] = cv[i] ^ (e & bi) ^ (av[i] & f);
+        st<NT>(z + (size_t)i * count + v, cv[i] ^ (e & bi) ^ (av[i] & f));
     }
 }
 
@@ -572,8 +573,11 @@ spin_status launch_bopen(const u64 *shares, const u64 *mask, size_t count, int n
     KernelTimer timer(SPIN_KERNEL_BINARY, s);
     for_party_count(n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
-        if (mask) bopen_kernel<NP, true><<<grid_for(count), kBlock, 0, s>>>(shares, mask, count, out);
-        else bopen_kernel<NP, false><<<grid_for(count), kBlock, 0, s>>>(shares, nullptr, count, out);
+        for_streaming((size_t)n * count * sizeof(u64), [&](auto nt) {
+            constexpr bool NT = decltype(nt)::value;
+            if (mask) bopen_kernel<NP, true, NT><<<grid_for(count), kBlock, 0, s>>>(shares, mask, count, out);
+            else bopen_kernel<NP, false, NT><<<grid_for(count), kBlock, 0, s>>>(shares, nullptr, count, out);
+        });
     });
     return check_launch("spin_bopen");
 }
@@ -583,7 +587,10 @@ spin_status launch_beaver_and(int n, size_t count, const u64 *x, const u64 *y, c
 {
     KernelTimer timer(SPIN_KERNEL_BINARY, s);
     for_party_count(n, [&](auto np) {
-        beaver_and_kernel<decltype(np)::value><<<grid_for(count), kBlock, 0, s>>>(x, y, a, b, c, count, z);
+        for_streaming((size_t)n * count * sizeof(u64), [&](auto nt) {
+            beaver_and_kernel<decltype(np)::value, decltype(nt)::value><<<grid_for(count), kBlock, 0, s>>>(
+                x, y, a, b, c, count, z);
+        });
     });
     return check_launch("spin_beaver_and");
 }

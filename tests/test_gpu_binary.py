@@ -45,3 +45,5 @@ def test_binary_and_at_config2_vector_length():
     a, b, c = oracle.dealer_and(n, count, seed=4)
     zd = spin.beaver_and(dev(xs), dev(ys), dev(a), dev(b), dev(c))
     assert (host(zd) == oracle.beaver_and(xs, ys, a, b, c)).all()
+    assert (host(spin.bopen(zd)) == (x & y)).all()                       # streaming-size open, plain and masked
+    assert (host(spin.bopen(zd, dev(a))) == oracle.bopen(host(zd), a)).all()
