@@ -104,6 +104,26 @@ spin_status spin_beaver_matmul_nt(int n, int batch, int M, int N, int K,
                                   uint64_t *Z, spin_gemm_path path,
                                   void *workspace, size_t workspace_bytes, spin_stream stream);
 
+/* An array of Beaver matmuls of different shapes in one call (Section 7.4's PMatMul takes arrays of
+ * matrices; products of one shape go into the batch dimension of a group, different shapes into
+ * different groups).  desc: HOST array of `groups` descriptors, read before the call returns; every
+ * group is what spin_beaver_matmul (y_transposed == 0) or spin_beaver_matmul_nt (!= 0) would be given,
+ * with the common party count n.  The groups are enqueued one after another on `stream` and share the
+ * workspace, which must hold the largest of them:
+ * spin_beaver_matmul_grouped_workspace_bytes(n, groups, desc, path), 0 if a descriptor is invalid.
+ * All descriptors are validated before the first launch.  1 <= groups <= SPIN_MAX_GROUPS.         */
+#define SPIN_MAX_GROUPS 64
+typedef struct {
+    int batch, M, N, K;
+    const uint64_t *X, *Y, *A, *B, *C;
+    uint64_t *Z;
+    int y_transposed;
+} spin_matmul_group;
+spin_status spin_beaver_matmul_grouped(int n, int groups, const spin_matmul_group *desc, spin_gemm_path path,
+                                       void *workspace, size_t workspace_bytes, spin_stream stream);
+size_t spin_beaver_matmul_grouped_workspace_bytes(int n, int groups, const spin_matmul_group *desc,
+                                                  spin_gemm_path path);
+
 /* Bytes of workspace spin_beaver_matmul needs; 0 if the arguments are invalid. */
 size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path);
 

@@ -138,6 +138,41 @@ spin_status spin_beaver_matmul_nt(int n, int batch, int M, int N, int K, const u
     return beaver_matmul64(n, batch, M, N, K, X, Yt, A, Bt, C, Z, path, workspace, workspace_bytes, stream, true);
 }
 
+size_t spin_beaver_matmul_grouped_workspace_bytes(int n, int groups, const spin_matmul_group *desc, spin_gemm_path path)
+{
+    if (desc == nullptr || groups < 1 || groups > SPIN_MAX_GROUPS) return 0;
+    size_t need = 0;
+    for (int g = 0; g < groups; ++g) {
+        const size_t b = spin_beaver_matmul_workspace_bytes(n, desc[g].batch, desc[g].M, desc[g].N, desc[g].K, path);
+        if (b == 0) return 0;
+        if (b > need) need = b;
+    }
+    return need;
+}
+
+spin_status spin_beaver_matmul_grouped(int n, int groups, const spin_matmul_group *desc, spin_gemm_path path,
+                                       void *workspace, size_t workspace_bytes, spin_stream stream)
+{
+    if (desc == nullptr || groups < 1 || groups > SPIN_MAX_GROUPS) return SPIN_EINVAL;
+    if (path != SPIN_GEMM_LIMB_MFMA && path != SPIN_GEMM_VALU) return SPIN_EINVAL;
+    for (int g = 0; g < groups; ++g) {                   // everything is checked before anything is launched
+        const spin_matmul_group &d = desc[g];
+        if (bad_ptr(d.X) || bad_ptr(d.Y) || bad_ptr(d.A) || bad_ptr(d.B) || bad_ptr(d.C) || bad_ptr(d.Z)) return SPIN_EINVAL;
+        spin_status st = check_matmul_dims(n, d.batch, d.M, d.N, d.K);
+        if (st != SPIN_OK) return st;
+    }
+    const size_t need = spin_beaver_matmul_grouped_workspace_bytes(n, groups, desc, path);
+    if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0 || need == 0 || workspace_bytes < need)
+        return SPIN_EWORKSPACE;
+    for (int g = 0; g < groups; ++g) {
+        const spin_matmul_group &d = desc[g];
+        spin_status st = beaver_matmul64(n, d.batch, d.M, d.N, d.K, d.X, d.Y, d.A, d.B, d.C, d.Z, path, workspace,
+                                         workspace_bytes, stream, d.y_transposed != 0);
+        if (st != SPIN_OK) return st;
+    }
+    return SPIN_OK;
+}
+
 spin_status spin_beaver_mul(int n, size_t count, const uint64_t *x, const uint64_t *y, const uint64_t *a,
                             const uint64_t *b, const uint64_t *c, uint64_t *z, spin_stream stream)
 {

@@ -37,6 +37,10 @@ def lib():
         L.spin_beaver_matmul.argtypes = [i32] * 5 + [p] * 6 + [i32, p, sz, p]
         L.spin_beaver_matmul_nt.argtypes = L.spin_beaver_matmul.argtypes
         L.spin_beaver_matmul_nt.restype = i32
+        L.spin_beaver_matmul_grouped.argtypes = [i32, i32, p, i32, p, sz, p]
+        L.spin_beaver_matmul_grouped.restype = i32
+        L.spin_beaver_matmul_grouped_workspace_bytes.argtypes = [i32, i32, p, i32]
+        L.spin_beaver_matmul_grouped_workspace_bytes.restype = sz
         L.spin_beaver_matmul_workspace_bytes.argtypes = [i32] * 5 + [i32]
         L.spin_beaver_matmul_workspace_bytes.restype = sz
         L.spin_beaver_mul.argtypes = [i32, sz] + [p] * 6 + [p]
@@ -156,6 +160,45 @@ def beaver_matmul(X, Y, A, B, C, path=LIMB_MFMA, out=None, workspace=None, y_tra
     _check(call(n, batch, M, N, K, _dev(X, "X"), _dev(Y, "Y"), _dev(A, "A"), _dev(B, "B"), _dev(C, "C"),
                 _dev(out, "Z"), path, workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
     return out
+
+
+class _MatmulGroup(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int), ("M", ctypes.c_int), ("N", ctypes.c_int), ("K", ctypes.c_int),
+                ("X", ctypes.c_void_p), ("Y", ctypes.c_void_p), ("A", ctypes.c_void_p), ("B", ctypes.c_void_p),
+                ("C", ctypes.c_void_p), ("Z", ctypes.c_void_p), ("y_transposed", ctypes.c_int)]
+
+
+def beaver_matmul_grouped(groups, path=LIMB_MFMA, workspace=None):
+    """groups: list of dicts with X, Y, A, B, C (as for beaver_matmul), optional out and y_transposed; shapes may
+    differ between groups, the party count may not.  Returns the list of Z tensors."""
+    n = groups[0]["X"].shape[0]
+    desc = (_MatmulGroup * len(groups))()
+    outs = []
+    for d, g in zip(desc, groups):
+        X, Y, A, B, C = g["X"], g["Y"], g["A"], g["B"], g["C"]
+        yt = bool(g.get("y_transposed", False))
+        nn, batch, M, K = X.shape
+        N = Y.shape[2] if yt else Y.shape[3]
+        yshape = (n, batch, N, K) if yt else (n, batch, K, N)
+        if nn != n or tuple(Y.shape) != yshape or A.shape != X.shape or B.shape != Y.shape \
+                or tuple(C.shape) != (n, batch, M, N):
+            raise SpinError("inconsistent operand shapes")
+        out = g.get("out")
+        if out is None:
+            out = torch.empty_like(C)
+        outs.append(out)
+        d.batch, d.M, d.N, d.K = batch, M, N, K
+        d.X, d.Y, d.A, d.B, d.C, d.Z = (_dev(t, k) for t, k in ((X, "X"), (Y, "Y"), (A, "A"), (B, "B"), (C, "C"), (out, "Z")))
+        d.y_transposed = 1 if yt else 0
+    L = lib()
+    need = int(L.spin_beaver_matmul_grouped_workspace_bytes(n, len(groups), desc, path))
+    if need == 0:
+        raise SpinError("invalid matmul dimensions")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=outs[0].device)
+    _check(L.spin_beaver_matmul_grouped(n, len(groups), desc, path, workspace.data_ptr(),
+                                        workspace.numel() * workspace.element_size(), _stream()))
+    return outs
 
 
 def beaver_mul(x, y, a, b, c, out=None):

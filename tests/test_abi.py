@@ -143,3 +143,28 @@ def test_validation_of_the_fused_multiplication(L):
     assert f(2, 8, 62, fake, fake, fake, fake, fake, fake, fake, fake, fake, None) == EINVAL
     assert f(2, 8, 16, fake, fake, fake, fake, fake, fake, None, fake, fake, None) == EINVAL
     assert f(2, 0, 16, fake, fake, fake, fake, fake, fake, fake, fake, fake, None) == EINVAL
+
+
+def test_validation_of_the_grouped_matmul(L):
+    from paper_2402_02320_amd.spin import _MatmulGroup
+    EINVAL, ERANGE, EWORKSPACE = 1, 2, 3
+    fake = 0x1000
+    desc = (_MatmulGroup * 2)()
+    for d in desc:
+        d.batch, d.M, d.N, d.K = 1, 8, 8, 8
+        d.X = d.Y = d.A = d.B = d.C = d.Z = fake
+    ws = ctypes.c_void_p(0x10000)
+    f, q = L.spin_beaver_matmul_grouped, L.spin_beaver_matmul_grouped_workspace_bytes
+    assert q(2, 2, desc, 0) == L.spin_beaver_matmul_workspace_bytes(2, 1, 8, 8, 8, 0)
+    assert f(2, 0, desc, 0, ws, 1 << 30, None) == EINVAL
+    assert f(2, 65, desc, 0, ws, 1 << 30, None) == EINVAL
+    assert f(2, 2, None, 0, ws, 1 << 30, None) == EINVAL
+    assert f(2, 2, desc, 0, ws, 16, None) == EWORKSPACE
+    desc[1].K = 0                                            # the second group is bad: nothing may be launched
+    assert f(2, 2, desc, 0, ws, 1 << 30, None) == EINVAL
+    assert q(2, 2, desc, 0) == 0
+    desc[1].K = 1 << 25
+    assert f(2, 2, desc, 0, ws, 1 << 30, None) == ERANGE
+    desc[1].K = 8
+    desc[1].Z = None
+    assert f(2, 2, desc, 0, ws, 1 << 30, None) == EINVAL

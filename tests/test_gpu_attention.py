@@ -150,3 +150,25 @@ def test_downsized_order_with_the_factor_tiled_inside_the_kernel():
     wtd, wto = trunc_both(wd.view(n, -1), wo, n, f, 23)
     got = oracle.decode(host(spin.open(wtd)), f).reshape(V.shape)
     assert np.abs(got - Rr[:, :, None] * V).max() <= 2.0 ** -f * 3 * max(1.0, np.abs(V).max())
+
+
+@pytest.mark.parametrize("path", [pytest.param(spin.LIMB_MFMA, id="limb"), pytest.param(spin.VALU, id="valu")])
+def test_grouped_matmuls_of_different_shapes_in_one_call(path):
+    # the attention products of three LeViT-like stages (196, 49 and 16 tokens) in one call: Q.K^T with K
+    # stored untransposed, then P.V; every group against the oracle
+    n = 3
+    rng = np.random.default_rng(77)
+    shapes = [(4, 196, 196, 64, True), (4, 196, 64, 196, False), (8, 49, 49, 32, True), (8, 49, 32, 49, False),
+              (12, 16, 16, 32, True), (1, 1, 1, 1, False)]
+    groups, wants = [], []
+    for idx, (batch, M, N, K, yt) in enumerate(shapes):
+        X = rng.integers(0, 1 << 64, size=(n, batch, M, K), dtype=np.uint64)
+        Y = rng.integers(0, 1 << 64, size=(n, batch, K, N), dtype=np.uint64)
+        A, B, C = oracle.dealer_matmul(n, batch, M, N, K, seed=700 + idx)
+        wants.append(oracle.beaver_matmul(X, Y, A, B, C))
+        if yt:
+            Y, B = np.ascontiguousarray(Y.transpose(0, 1, 3, 2)), np.ascontiguousarray(B.transpose(0, 1, 3, 2))
+        groups.append({"X": dev(X), "Y": dev(Y), "A": dev(A), "B": dev(B), "C": dev(C), "y_transposed": yt})
+    outs = spin.beaver_matmul_grouped(groups, path=path)
+    for z, want in zip(outs, wants):
+        assert (host(z) == want).all()
