@@ -5,7 +5,8 @@
  * products, and fixed-point truncation (spin_share, spin_open,
  * spin_beaver_matmul, spin_beaver_mul, spin_trunc).  Further down: the same
  * over Z_2^32 and Z_2^128 (spin32_*, spin128_*), binary shares (spin_b*),
- * a public linear combination with fused truncation, and measurement aids.
+ * and a public linear combination with fused truncation.  Measurement aids
+ * (per-kernel event timing, an MFMA rate probe) are declared in spin_bench.h.
  *
  * Conventions that hold for every entry point
  * -------------------------------------------
@@ -16,9 +17,11 @@
  *    T[i] is party i's share, contiguous, so a tensor of `count` elements is
  *    laid out [n][count].  Party 0 is the paper's party 1: it holds residual
  *    shares and adds every public term.
- *  - Every data pointer is a DEVICE pointer, 16-byte aligned, owned by the
- *    caller; the library never allocates, frees or keeps a pointer.  Buffers
- *    must not overlap unless a function says an output may alias an input.
+ *  - Every data pointer is a DEVICE pointer, 16-byte aligned (the widest vector
+ *    access any kernel makes; workspaces 256-byte), owned by the caller; the
+ *    entry points of this header never allocate, free or keep a pointer.
+ *    Buffers must not overlap unless a function says an output may alias an
+ *    input.
  *  - Calls are asynchronous: work is enqueued on `stream` (a hipStream_t; NULL
  *    is the default stream) and the function returns without synchronising.
  *  - Errors are return codes.  Arguments are validated before anything is
@@ -265,46 +268,6 @@ spin_status spin32_trunc(int n, size_t count, int f, const uint32_t *x,
                          const uint32_t *r, const uint32_t *r_top, const uint32_t *r_msb,
                          uint32_t *out, spin_stream stream);
 spin_status spin_cast_64_to_32(const uint64_t *in, size_t count, uint32_t *out, spin_stream stream);
-
-/* Per-kernel timing for benchmarks (measurement aid, not part of the protocol).
- * While enabled, every kernel the library launches is bracketed by a pair of
- * HIP events recorded on the caller's stream; events are created on demand
- * (this is the one place the library allocates, and only while enabled).
- * spin_profile_read waits for the recorded events, and returns the summed
- * duration in milliseconds and the number of launches of one kernel class
- * since the last spin_profile_reset.  Not thread-safe; leave it disabled while a
- * stream is being captured into a HIP graph (recorded events cannot be timed). */
-typedef enum {
-    SPIN_KERNEL_RANDOM = 0,
-    SPIN_KERNEL_SHARE = 1,
-    SPIN_KERNEL_OPEN = 2,
-    SPIN_KERNEL_BEAVER_MUL = 3,
-    SPIN_KERNEL_TRUNC = 4,
-    SPIN_KERNEL_PACK = 5,       /* open + digit split + fragment layout for the limb GEMM */
-    SPIN_KERNEL_GEMM_LIMB = 6,
-    SPIN_KERNEL_GEMM_VALU = 7,
-    SPIN_KERNEL_LINCOMB = 8,
-    SPIN_KERNEL_BINARY = 9,     /* bshare, bopen, beaver_and */
-    SPIN_KERNEL_CAST = 10,      /* spin_cast_64_to_32 */
-    SPIN_KERNEL_PROBE = 11,     /* spin_probe_mfma */
-    SPIN_KERNEL_MUL_TRUNC = 12, /* spin_beaver_mul_trunc */
-    SPIN_KERNEL_COUNT = 13
-} spin_kernel;
-void spin_profile_enable(int on);
-spin_status spin_profile_read(spin_kernel kernel, double *total_ms, unsigned *launches);
-void spin_profile_reset(void);
-
-/* Measurement aid: the int8 matrix-core rate the chip sustains on given operand bytes.  Every wave
- * of `blocks` workgroups (4 waves each) loads 24 MFMA operand fragments of 1 KiB from `operands`
- * ([24][128] uint64_t: 16 left fragments for two 32x32 tiles, then 8 right fragments; lane l of a wave
- * reads bytes 16 l .. 16 l + 15 of each) and issues, `iters` times, the 72 v_mfma_i32_32x32x32_i8 of one
- * k-step of the 64-bit limb GEMM (digit pairs i + j <= 7, pairs of one diagonal sharing an
- * accumulator), with no memory or LDS access inside the loop: blocks * 4 * iters * 72 * 65536 int8
- * operations per call.  sink[blocks * 256] receives each thread's wrapped int32 sum of its
- * accumulator registers, sign-extended (it keeps the loop alive and lets a test check the
- * arithmetic).  1 <= blocks <= 2^20, 1 <= iters <= 2^20.  Time it with spin_profile_* or events.  */
-spin_status spin_probe_mfma(const uint64_t *operands, int blocks, int iters, uint64_t *sink,
-                            spin_stream stream);
 
 /* Static description of a status code. */
 const char *spin_status_string(spin_status status);

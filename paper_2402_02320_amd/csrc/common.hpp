@@ -8,7 +8,7 @@
 
 #include <type_traits>
 
-#include "../../include/spin.h"
+#include "../../include/spin_bench.h"
 
 namespace spin {
 
@@ -54,15 +54,26 @@ template <class F> inline void for_party_count(int n, F &&fn)
 
 // ---- launch bookkeeping ------------------------------------------------------
 void note_hip_error(hipError_t e, const char *where);
-// Returns SPIN_OK or records the launch error and returns SPIN_EHIP.
+// Returns SPIN_OK or records the launch error and returns SPIN_EHIP.  Only errors raised since the
+// enclosing KernelTimer was constructed are seen (it discards whatever an earlier, unrelated HIP call left).
 spin_status check_launch(const char *where);
 
-// Brackets the launches made during its lifetime with a HIP event pair when profiling is enabled.
+// Every launcher constructs one before its launches.  It clears the runtime's sticky last-error slot, so
+// that check_launch reports this launch only, and, when profiling is enabled and the stream is not being
+// captured into a graph, brackets the launches made during its lifetime with a HIP event pair.
 struct KernelTimer {
     KernelTimer(spin_kernel id, hipStream_t s);
     ~KernelTimer();
     spin_kernel id; hipStream_t stream; hipEvent_t begin; bool active;
 };
+
+// Per-device facts and one-time set-up, indexed by the current device.
+constexpr int kMaxDevices = 64;
+int current_device();                 // hipGetDevice, clamped to [0, kMaxDevices)
+int compute_units();                  // of the current device (256 when the runtime cannot say)
+// Raises a kernel's dynamic-LDS limit once per device; `done` is that kernel's per-device flag array.
+struct OncePerDevice { unsigned char done[kMaxDevices]; };
+spin_status allow_dynamic_lds(const void *kernel, int bytes, OncePerDevice &flags);
 
 // ---- internal launchers (defined in the .hip files) -------------------------
 spin_status launch_random(u64 *out, size_t count, u64 key, u64 first_idx, hipStream_t s);

@@ -186,10 +186,11 @@ __global__ __launch_bounds__(kBlock) void beaver_mul_bcast_kernel(const u64 *__r
 }
 
 // The combine of the signed probabilistic truncation (Section 4.4) on party shares y[] held in
-// registers; steps as listed at spin_trunc in include/spin.h.
+// registers; steps as listed at spin_trunc in include/spin.h.  Every tuple word is read before the first
+// store, and no pointer is declared restrict, so `out` may be any of the inputs.
 template <int NP, class T, bool NT>
-__device__ inline void truncate_and_store(const T (&y)[NP], const T *__restrict__ r, const T *__restrict__ r_top,
-                                          const T *__restrict__ r_msb, size_t count, size_t v, int f, T *out)
+__device__ inline void truncate_and_store(const T (&y)[NP], const T *r, const T *r_top, const T *r_msb, size_t count,
+                                          size_t v, int f, T *out)
 {
     constexpr int L = Lanes<T>::bits;              // ring width l
     T rt[NP], rm[NP];
@@ -213,8 +214,7 @@ __device__ inline void truncate_and_store(const T (&y)[NP], const T *__restrict_
 }
 
 template <int NP, class T, bool NT>
-__global__ __launch_bounds__(kBlock) void trunc_kernel(const T *x, const T *__restrict__ r,
-                                                      const T *__restrict__ r_top, const T *__restrict__ r_msb,
+__global__ __launch_bounds__(kBlock) void trunc_kernel(const T *x, const T *r, const T *r_top, const T *r_msb,
                                                       size_t count, int f, T *out)
 {
     size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
@@ -231,11 +231,9 @@ __global__ __launch_bounds__(kBlock) void trunc_kernel(const T *x, const T *__re
 // instead of 6n + 5n.
 template <int NP, bool NT>
 __global__ __launch_bounds__(kBlock) void beaver_mul_trunc_kernel(const u64 *x, const u64 *y, const u64 *a,
-                                                                 const u64 *b, const u64 *c,
-                                                                 const u64 *__restrict__ r,
-                                                                 const u64 *__restrict__ r_top,
-                                                                 const u64 *__restrict__ r_msb, size_t count, int f,
-                                                                 u64 *out)
+                                                                 const u64 *b, const u64 *c, const u64 *r,
+                                                                 const u64 *r_top, const u64 *r_msb, size_t count,
+                                                                 int f, u64 *out)
 {
     size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (v >= count) return;
@@ -262,9 +260,8 @@ __global__ __launch_bounds__(kBlock) void beaver_mul_trunc_kernel(const u64 *x, 
 // (Section 4.3 Addition/Scaling; Section 4.4 Polynomial evaluation: one deferred truncation).
 // The term loop is a run-time loop; every iteration issues one load per party.
 template <int NP, bool TRUNC, bool NT>
-__global__ __launch_bounds__(kBlock) void lincomb_trunc_kernel(LincombTerms t, u64 constant, const u64 *__restrict__ r,
-                                                              const u64 *__restrict__ r_top,
-                                                              const u64 *__restrict__ r_msb, size_t count, int f,
+__global__ __launch_bounds__(kBlock) void lincomb_trunc_kernel(LincombTerms t, u64 constant, const u64 *r,
+                                                              const u64 *r_top, const u64 *r_msb, size_t count, int f,
                                                               u64 *out)
 {
     size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;

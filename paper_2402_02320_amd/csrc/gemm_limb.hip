@@ -25,30 +25,18 @@
 //                32x32x32 step into 8 diagonal accumulators, recombined once.
 #include "limb_common.hpp"
 
-// Interleave of one k-step of the 64-bit GEMM (slots = MFMA index within the step, 72 per step for the
-// 64x32 wave tile): an LDS read after every RD_EVERY-th MFMA from slot 0, a direct-to-LDS load after
-// every LD_EVERY-th MFMA from slot LD_FIRST.
-#ifndef SPIN_TUNE_RD_EVERY
-#define SPIN_TUNE_RD_EVERY 2
-#endif
-#ifndef SPIN_TUNE_LD_FIRST
-#define SPIN_TUNE_LD_FIRST 13
-#endif
-#ifndef SPIN_TUNE_LD_EVERY
-#define SPIN_TUNE_LD_EVERY 4
-#endif
-
 namespace spin {
 namespace {
 
 // Per ring: digits, workgroup shape (waves are 2 x 2, each WM x WN MFMA tiles of 32 x 32; ND * WM * WN
-// * 16 accumulator registers <= 256), longest run of k-tiles one launch may accumulate, and the slots
-// of the interleave.
+// * 16 accumulator registers <= 256), longest run of k-tiles one launch may accumulate, and the
+// interleave of one k-step (slots = MFMA index within the step): an LDS read after every rd_every-th
+// MFMA from slot 0, a direct-to-LDS load after every ld_every-th MFMA from slot ld_first.
 template <class T> struct Ring;
 template <> struct Ring<u64> {
     static constexpr int WM = 2, WN = 1;
     static constexpr int max_chunk_tiles = 511;        // 2*511*32 = 32704 < 2^15 digit products per accumulator
-    static constexpr int rd_every = SPIN_TUNE_RD_EVERY, ld_first = SPIN_TUNE_LD_FIRST, ld_every = SPIN_TUNE_LD_EVERY;
+    static constexpr int rd_every = 2, ld_first = 13, ld_every = 4;   // 72 MFMAs, 24 reads, 12 loads per step
 };
 template <> struct Ring<u32> {
     static constexpr int WM = 2, WN = 2;
@@ -351,15 +339,7 @@ template <class T> inline Plan make_plan(int n, int batch, int M, int N, int K)
 // their parts onto Z atomically) shortens the rounds.  Returns the count that minimises that model.
 inline int choose_splits(long tiles, int steps)
 {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            cus = v;
-        else
-            cus = 256;
-    }
+    const int cus = compute_units();
     constexpr int kFixedCost = 8;                        // prologue + epilogue, in k-step equivalents
     constexpr int kMinSteps = 8;                         // shorter parts are all overhead
     long best_cost = -1;
@@ -385,14 +365,10 @@ template <class T> spin_status launch_limb(const MatmulArgsT<T> &a, hipStream_t 
     spin_status st = check_launch(where_pack);
     if (st != SPIN_OK) return st;
 
-    static bool attr_set = false;                        // one flag per ring type
+    static OncePerDevice lds_allowed;                    // one per ring type
     auto kernel = limb_gemm_kernel<T>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           S::lds_bytes);
-        if (e != hipSuccess) { note_hip_error(e, "hipFuncSetAttribute"); return SPIN_EHIP; }
-        attr_set = true;
-    }
+    st = allow_dynamic_lds((const void *)kernel, S::lds_bytes, lds_allowed);
+    if (st != SPIN_OK) return st;
     GemmArgs<T> g{packA, packB, a.C, a.Z, a.n, a.batch, a.M, a.N, p.nblkA, p.nblkB, p.KT, 0, 0, p.tilesM, p.tilesN,
                   1, 0};
     const long total = (long)p.tilesM * p.tilesN * a.n * a.batch;
@@ -414,8 +390,10 @@ template <class T> spin_status launch_limb(const MatmulArgsT<T> &a, hipStream_t 
         if (splits > 1 && used == 1) g.C = a.Z;          // a short last chunk in one part: plain accumulate onto Z
         KernelTimer timer(SPIN_KERNEL_GEMM_LIMB, s);
         kernel<<<(unsigned)(total * used), 256, S::lds_bytes, s>>>(g);
+        st = check_launch(where_gemm);
+        if (st != SPIN_OK) return st;
     }
-    return check_launch(where_gemm);
+    return SPIN_OK;
 }
 
 }  // namespace

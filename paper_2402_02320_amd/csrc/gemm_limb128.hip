@@ -198,13 +198,9 @@ spin_status launch_matmul_limb128(const MatmulArgs128 &a, hipStream_t s)
     spin_status st = check_launch("spin128_beaver_matmul(pack)");
     if (st != SPIN_OK) return st;
 
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)limb128_gemm_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, Shape128::lds_bytes);
-        if (e != hipSuccess) { note_hip_error(e, "hipFuncSetAttribute"); return SPIN_EHIP; }
-        attr_set = true;
-    }
+    static OncePerDevice lds_allowed;
+    st = allow_dynamic_lds((const void *)limb128_gemm_kernel, Shape128::lds_bytes, lds_allowed);
+    if (st != SPIN_OK) return st;
     Gemm128Args g{packA, packB, a.C, a.Z, a.n, a.batch, a.M, a.N, p.nblkA, p.nblkB, p.KT, 0, 0, p.tilesM, p.tilesN};
     const long total = (long)p.tilesM * p.tilesN * a.n * a.batch;
     for (int kt0 = 0; kt0 < p.KT; kt0 += kMaxChunkTiles128) {
@@ -213,8 +209,10 @@ spin_status launch_matmul_limb128(const MatmulArgs128 &a, hipStream_t s)
         g.C = kt0 == 0 ? a.C : a.Z;                      // later chunks accumulate onto Z
         KernelTimer timer(SPIN_KERNEL_GEMM_LIMB, s);
         limb128_gemm_kernel<<<(unsigned)total, 256, Shape128::lds_bytes, s>>>(g);
+        st = check_launch("spin128_beaver_matmul(limb gemm)");
+        if (st != SPIN_OK) return st;
     }
-    return check_launch("spin128_beaver_matmul(limb gemm)");
+    return SPIN_OK;
 }
 
 }  // namespace spin

@@ -288,10 +288,14 @@ __global__ __launch_bounds__(64 * WAVES) void pack_left_kernel(PackArgs<T> a)
 // One direct-to-LDS load: 64 lanes x 16 bytes from src + lane*16 to the LDS address lds_dst + lane*16.
 // Issued through inline assembly so that the compiler's LDS-DMA bookkeeping does not serialise the
 // software pipeline; completion is awaited explicitly (wait_loads) before the workgroup barrier.
+// The instruction takes its LDS base from m0, a register the compiler reserves for its own use and
+// does not accept in a clobber list, so the statement puts back the value it found there (m0 is read
+// when the load issues, so restoring it right after is safe).
 __device__ inline void load_fragment_to_lds(const char *src, u32 lds_dst, u32 lane16)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(lane16), "s"(src), "s"(lds_dst) : "memory");
+    u32 saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "v"(lane16), "s"(src), "s"(lds_dst) : "memory");
 }
 template <int N> __device__ inline void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 __device__ inline void wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }

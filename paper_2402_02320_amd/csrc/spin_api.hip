@@ -3,6 +3,8 @@
 // a machine without a GPU.
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
 #include <vector>
 
 #include "common.hpp"
@@ -24,16 +26,55 @@ spin_status check_launch(const char *where)
     return SPIN_EHIP;
 }
 
+// ---- per-device facts ------------------------------------------------------------
+int current_device()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
+    return dev;
+}
+
+int compute_units()
+{
+    static std::atomic<int> cus[kMaxDevices];            // zero-initialised; a race only repeats the query
+    const int dev = current_device();
+    int v = cus[dev].load(std::memory_order_relaxed);
+    if (v == 0) {
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+        cus[dev].store(v, std::memory_order_relaxed);
+    }
+    return v;
+}
+
+spin_status allow_dynamic_lds(const void *kernel, int bytes, OncePerDevice &flags)
+{
+    static std::mutex m;
+    const int dev = current_device();
+    std::lock_guard<std::mutex> lock(m);
+    if (flags.done[dev]) return SPIN_OK;
+    hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) { note_hip_error(e, "hipFuncSetAttribute"); return SPIN_EHIP; }
+    flags.done[dev] = 1;
+    return SPIN_OK;
+}
+
 // ---- optional per-kernel event timing ---------------------------------------
 namespace {
 struct TimedLaunch { spin_kernel id; hipEvent_t begin, end; };
-bool g_profile = false;
+std::atomic<bool> g_profile{false};
+std::mutex g_timed_mutex;
 std::vector<TimedLaunch> g_timed;
 }  // namespace
 
 KernelTimer::KernelTimer(spin_kernel id_, hipStream_t s) : id(id_), stream(s), begin(nullptr), active(false)
 {
-    if (!g_profile) return;
+    (void)hipGetLastError();                             // a stale error of an earlier call is not this launch's
+    if (!g_profile.load(std::memory_order_relaxed)) return;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
+        (void)hipGetLastError();
+        return;
+    }
     if (hipEventCreate(&begin) != hipSuccess) return;
     active = hipEventRecord(begin, stream) == hipSuccess;
     if (!active) (void)hipEventDestroy(begin);
@@ -43,8 +84,10 @@ KernelTimer::~KernelTimer()
 {
     if (!active) return;
     hipEvent_t end;
-    if (hipEventCreate(&end) == hipSuccess && hipEventRecord(end, stream) == hipSuccess)
-        g_timed.push_back({id, begin, end});
+    if (hipEventCreate(&end) != hipSuccess) { (void)hipEventDestroy(begin); return; }
+    if (hipEventRecord(end, stream) != hipSuccess) { (void)hipEventDestroy(begin); (void)hipEventDestroy(end); return; }
+    std::lock_guard<std::mutex> lock(g_timed_mutex);
+    g_timed.push_back({id, begin, end});
 }
 
 namespace {
@@ -107,14 +150,22 @@ size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K,
     return 0;
 }
 
+// Everything spin_beaver_matmul checks except the workspace; touches no HIP call.
+static spin_status check_matmul64(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Y,
+                                  const uint64_t *A, const uint64_t *B, const uint64_t *C, uint64_t *Z,
+                                  spin_gemm_path path)
+{
+    if (bad_ptr(X) || bad_ptr(Y) || bad_ptr(A) || bad_ptr(B) || bad_ptr(C) || bad_ptr(Z)) return SPIN_EINVAL;
+    if (path != SPIN_GEMM_LIMB_MFMA && path != SPIN_GEMM_VALU) return SPIN_EINVAL;
+    return check_matmul_dims(n, batch, M, N, K);
+}
+
 static spin_status beaver_matmul64(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Y,
                                    const uint64_t *A, const uint64_t *B, const uint64_t *C, uint64_t *Z,
                                    spin_gemm_path path, void *workspace, size_t workspace_bytes, spin_stream stream,
                                    bool y_transposed)
 {
-    if (bad_ptr(X) || bad_ptr(Y) || bad_ptr(A) || bad_ptr(B) || bad_ptr(C) || bad_ptr(Z)) return SPIN_EINVAL;
-    if (path != SPIN_GEMM_LIMB_MFMA && path != SPIN_GEMM_VALU) return SPIN_EINVAL;
-    spin_status st = check_matmul_dims(n, batch, M, N, K);
+    spin_status st = check_matmul64(n, batch, M, N, K, X, Y, A, B, C, Z, path);
     if (st != SPIN_OK) return st;
     const size_t need = spin_beaver_matmul_workspace_bytes(n, batch, M, N, K, path);
     if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need)
@@ -216,10 +267,11 @@ spin_status spin_trunc(int n, size_t count, int f, const uint64_t *x, const uint
     return launch_trunc(n, count, f, x, r, r_top, r_msb, out, (hipStream_t)stream);
 }
 
-void spin_profile_enable(int on) { g_profile = on != 0; }
+void spin_profile_enable(int on) { g_profile.store(on != 0); }
 
 void spin_profile_reset(void)
 {
+    std::lock_guard<std::mutex> lock(g_timed_mutex);
     for (auto &t : g_timed) { (void)hipEventDestroy(t.begin); (void)hipEventDestroy(t.end); }
     g_timed.clear();
 }
@@ -229,6 +281,7 @@ spin_status spin_profile_read(spin_kernel kernel, double *total_ms, unsigned *la
     if (!total_ms || !launches || kernel < 0 || kernel >= SPIN_KERNEL_COUNT) return SPIN_EINVAL;
     double sum = 0.0;
     unsigned cnt = 0;
+    std::lock_guard<std::mutex> lock(g_timed_mutex);
     for (auto &t : g_timed) {
         if (t.id != kernel) continue;
         hipError_t e = hipEventSynchronize(t.end);

@@ -1,5 +1,5 @@
-"""The C-ABI library loads without a GPU, exports every symbol include/spin.h
-declares, and rejects bad arguments before any launch."""
+"""The C-ABI library loads without a GPU, exports every symbol include/*.h
+declare, and rejects bad arguments before any launch."""
 import ctypes
 import os
 import re
@@ -19,9 +19,14 @@ def L():
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "spin.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(spin[0-9]*_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if not header.endswith(".h"):
+            continue
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(spin[0-9]*_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_five_calls():

@@ -25,9 +25,11 @@ def compile_cmd(out, syntax_only=False):
 
 
 def test_header_is_valid_c_and_cxx():
-    hdr = os.path.join(ROOT, "include", "spin.h")
-    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c", hdr], check=True)
-    subprocess.run(["g++", "-std=c++11", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", hdr], check=True)
+    for name in ("spin.h", "spin_bench.h"):
+        hdr = os.path.join(ROOT, "include", name)
+        subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c", hdr], check=True)
+        subprocess.run(["g++", "-std=c++11", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", hdr],
+                       check=True)
 
 
 def test_c_harness_compiles():

@@ -1,8 +1,9 @@
 """GPU-vs-oracle parity through the C ABI: every share bit-exact on the same
 seeded inputs, at sizes that span several tiles and a ragged tail, on the edge
-cases, and at the benchmark's full sizes (sampled rows where the oracle would
-take too long).  Inputs and expected values come from oracle/ and the workload
-generators only."""
+cases, and at the full size of every benchmark configuration (whole tensors:
+every share word of the product and of the truncated product, the
+reconstruction and the decoded bound over every row).  Inputs and expected
+values come from oracle/ and the workload generators only."""
 import numpy as np
 import pytest
 import torch
@@ -233,8 +234,9 @@ def encode_share(x, n, f, seed, stream):
     return oracle.share(oracle.encode(x, f), n, seed, stream)
 
 
-def fixed_point_pipeline(cfg, gemm_index, X_real, Y_real, path, rows=None):
-    """share -> Beaver matmul -> trunc on the GPU vs the oracle; returns decoded GPU result."""
+def fixed_point_pipeline(cfg, gemm_index, X_real, Y_real, path, rows=None, cross_path=None):
+    """share -> Beaver matmul -> trunc on the GPU vs the oracle; returns the largest decoded error.
+    rows = None compares whole tensors.  cross_path: a second GEMM path whose whole Z must equal the first's."""
     c = workloads.CONFIGS[cfg]
     n, f = c.n, c.f
     batch, M, K = X_real.shape
@@ -246,7 +248,11 @@ def fixed_point_pipeline(cfg, gemm_index, X_real, Y_real, path, rows=None):
     X, Y = oracle.share(xe, n, c.seed, oracle.STREAM_X), oracle.share(ye, n, c.seed, oracle.STREAM_Y)
     assert (host(Xd) == X).all() and (host(Yd) == Y).all()
     A, B, C = oracle.dealer_matmul(n, batch, M, N, K, seed=c.seed)
-    Zd = spin.beaver_matmul(Xd, Yd, dev(A), dev(B), dev(C), path=path)
+    Ad, Bd, Cd = dev(A), dev(B), dev(C)
+    Zd = spin.beaver_matmul(Xd, Yd, Ad, Bd, Cd, path=path)
+    if cross_path is not None:
+        assert torch.equal(Zd, spin.beaver_matmul(Xd, Yd, Ad, Bd, Cd, path=cross_path))
+    del Ad, Bd, Cd
     Zg = host(Zd)
     if rows is None:
         Zo = oracle.beaver_matmul(X, Y, A, B, C)
@@ -313,12 +319,12 @@ def test_config3_conv_shape_eighth_batch(path):
     fixed_point_pipeline(3, 0, X, Y, path)
 
 
-def test_config3_conv_shape_full_sampled_rows():
+def test_config3_conv_shape_full():
+    # the whole 131072 x 576 x 64 product of 3 parties, the launch the benchmark times: every share word of Z and
+    # of the truncated Z against the oracle, the reconstruction and the decoded bound over every row
     X, Y = workloads.gemm_plaintexts(3)
     assert X.shape == (1, 131072, 576)
-    rows = np.sort(np.random.default_rng(33).choice(131072, 512, replace=False))
-    rows[0], rows[-1] = 0, 131071
-    fixed_point_pipeline(3, 0, X, Y, spin.LIMB_MFMA, rows=rows)
+    fixed_point_pipeline(3, 0, X, Y, spin.LIMB_MFMA, cross_path=spin.VALU)
 
 
 @pytest.mark.parametrize("path", PATHS)
@@ -343,13 +349,13 @@ def test_config4_score_tensor_elementwise():
     assert (host(spin.beaver_mul(dev(X), dev(Y), dev(a), dev(b), dev(cc))) == zo).all()
 
 
-def test_config5_full_size_sampled_rows():
-    # 5 parties, 4096^3, the launch the benchmark times.  The oracle computes 96 sampled rows of every
-    # party's share; all other steps (sharing, truncation on those rows, reconstruction) are checked too.
+def test_config5_full():
+    # 5 parties, 4096^3, the launch the benchmark times, compared whole: every one of the 5 x 2^24 share words of
+    # Z and of the truncated Z against the oracle (about 8e11 ring multiply-adds on the host cores), the sum of
+    # the shares against the plain ring product, the decoded result against float64 over every row, and the
+    # baseline GEMM path against the limb path over the whole of Z.
     X, Y = workloads.gemm_plaintexts(5)
-    rows = np.sort(np.random.default_rng(55).choice(4096, 96, replace=False))
-    rows[0], rows[-1] = 0, 4095
-    fixed_point_pipeline(5, 0, X, Y, spin.LIMB_MFMA, rows=rows)
+    fixed_point_pipeline(5, 0, X, Y, spin.LIMB_MFMA, cross_path=spin.VALU)
 
 
 def test_paths_agree_on_config5_shape_slice():

@@ -298,6 +298,31 @@ def test_trunc_64_bit_closed_form(n, f):
         assert 0.45 < np.mean(vs) < 0.55
 
 
+@pytest.mark.parametrize("n,f,l", [(2, 16, 64), (3, 16, 64), (5, 26, 64), (3, 1, 64), (2, 61, 64), (3, 3, 8), (4, 5, 16)])
+def test_trunc_every_partys_share_against_python_integers(n, f, l):
+    # The sum alone does not fix which party adds the public terms.  Section 4.4's signed wrapper around the
+    # mask-and-open UnsignedTruncate, with the reading that party 0 (the paper's party 1) adds every public
+    # term, written out per party in exact integers:
+    #   c = sum_i (x_i + r_i) + 2^(l-2);  c_msb = bit l-1 of c;  c' = bits f..l-2 of c
+    #   out_i = -r_top_i + 2^(l-1-f) (r_msb_i - 2 c_msb r_msb_i)              for every party, and
+    #   out_0 += c' + 2^(l-1-f) c_msb - 2^(l-2-f)                              for party 0 only.
+    q = 1 << l
+    rng = np.random.default_rng(1000 * n + 10 * f + l)
+    L = 300
+    X, R, RT, RM = (rng.integers(0, q, size=(n, L), dtype=np.uint64) for _ in range(4))   # arbitrary share words
+    out = oracle.trunc(X, R, RT, RM, f, l=l)
+    for k in range(L):
+        x, r, rt, rm = ([int(t[i, k]) for i in range(n)] for t in (X, R, RT, RM))
+        c = (sum(x) + sum(r) + (1 << (l - 2))) % q
+        c_msb = c >> (l - 1)
+        c_top = (c >> f) % (1 << (l - 1 - f))
+        for i in range(n):
+            want = -rt[i] + (1 << (l - 1 - f)) * (rm[i] - 2 * c_msb * rm[i])
+            if i == 0:
+                want += c_top + (1 << (l - 1 - f)) * c_msb - (1 << (l - 2 - f))
+            assert int(out[i, k]) == want % q, (i, k)
+
+
 def test_trunc_out_of_range_input_is_wrong_as_the_paper_warns():
     # x outside [-2^(l-2), 2^(l-2)-1] makes x + 2^(l-2) use the top bit and UnsignedTruncate stops
     # working (Section 4.4).  On l = 8, f = 3, x = 100: x' = 164 = 128 + 36, and the result is off by
