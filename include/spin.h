@@ -130,6 +130,23 @@ size_t spin_beaver_matmul_grouped_workspace_bytes(int n, int groups, const spin_
 /* Bytes of workspace spin_beaver_matmul needs; 0 if the arguments are invalid. */
 size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path);
 
+/* spin_beaver_matmul for callers that cannot allocate device memory, and so cannot bring a workspace:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * operands, result and checks as spin_beaver_matmul; the workspace is an array of
+ * SPIN_STATIC_WORKSPACE_BYTES inside the library's device image (each GPU the library runs on holds its
+ * copy until the process ends).  The call allocates and frees nothing -- no device or host memory, no
+ * event objects (per-kernel timing is not recorded for it) -- and only enqueues kernels on `stream`.
+ * Returns SPIN_EWORKSPACE, before anything is launched, when
+ * spin_beaver_matmul_workspace_bytes(n, batch, M, N, K, path) exceeds SPIN_STATIC_WORKSPACE_BYTES.
+ * All calls on one GPU share that GPU's array: two calls whose kernels may overlap in time (different
+ * streams, or two replays of graphs that contain it) race and give wrong results; calls on one stream,
+ * one after another, are safe.  The first call on a device looks the array's address up.          */
+#define SPIN_STATIC_WORKSPACE_BYTES (64u << 20)
+spin_status spin_beaver_matmul_static(int n, int batch, int M, int N, int K,
+                                      const uint64_t *X, const uint64_t *Y,
+                                      const uint64_t *A, const uint64_t *B, const uint64_t *C,
+                                      uint64_t *Z, spin_gemm_path path, spin_stream stream);
+
 /* Online phase of elementwise multiplication with scalar triples (Section 4.3;
  * the "batch multiplication" of Section 7.3):
  *     e = sum_i (x_i - a_i), f = sum_i (y_i - b_i),

@@ -66,10 +66,14 @@ std::mutex g_timed_mutex;
 std::vector<TimedLaunch> g_timed;
 }  // namespace
 
+// > 0 while this thread is inside an entry point that must not allocate: no event objects are created then
+static thread_local int g_no_timing = 0;
+struct NoTimingScope { NoTimingScope() { ++g_no_timing; } ~NoTimingScope() { --g_no_timing; } };
+
 KernelTimer::KernelTimer(spin_kernel id_, hipStream_t s) : id(id_), stream(s), begin(nullptr), active(false)
 {
     (void)hipGetLastError();                             // a stale error of an earlier call is not this launch's
-    if (!g_profile.load(std::memory_order_relaxed)) return;
+    if (g_no_timing > 0 || !g_profile.load(std::memory_order_relaxed)) return;
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
         (void)hipGetLastError();
@@ -222,6 +226,61 @@ spin_status spin_beaver_matmul_grouped(int n, int groups, const spin_matmul_grou
         if (st != SPIN_OK) return st;
     }
     return SPIN_OK;
+}
+
+}  // extern "C"
+
+// ---- the entry point that allocates nothing ----------------------------------------------------
+// The workspace of spin_beaver_matmul_static lives in the library's own device image: every GPU the
+// library runs on holds one copy of this array, at its own address, until the process ends.  In host
+// code the array's name is only a handle for the runtime's symbol lookup, never a device address: the
+// address is asked for once per device (with that device current) and only that pointer is handed to
+// kernels.
+namespace {
+static __device__ __align__(256) unsigned char scratch[SPIN_STATIC_WORKSPACE_BYTES];
+void *g_scratch_ptr[spin::kMaxDevices];                  // device address of `scratch`, per device
+std::mutex g_scratch_mutex;
+
+spin_status static_workspace(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { note_hip_error(e, "hipGetDevice"); return SPIN_EHIP; }
+    if (dev < 0 || dev >= spin::kMaxDevices) { note_hip_error(hipErrorInvalidDevice, "spin_beaver_matmul_static"); return SPIN_EHIP; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || ptr == nullptr) {
+            note_hip_error(e != hipSuccess ? e : hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+            return SPIN_EHIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SPIN_OK;
+}
+}  // namespace
+
+extern "C" {
+
+spin_status spin_beaver_matmul_static(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Y,
+                                      const uint64_t *A, const uint64_t *B, const uint64_t *C, uint64_t *Z,
+                                      spin_gemm_path path, spin_stream stream)
+{
+    spin_status st = check_matmul64(n, batch, M, N, K, X, Y, A, B, C, Z, path);
+    if (st != SPIN_OK) return st;
+    const size_t need = spin_beaver_matmul_workspace_bytes(n, batch, M, N, K, path);
+    if (need == 0 || need > (size_t)SPIN_STATIC_WORKSPACE_BYTES) return SPIN_EWORKSPACE;
+    void *ws = nullptr;
+    st = static_workspace(&ws);
+    if (st != SPIN_OK) return st;
+    NoTimingScope no_events;                             // event timing would create event objects
+    // Nothing in the workspace has to start at zero: the pack kernels (limb path) and the opening of E and F
+    // (baseline path) overwrite every byte a later kernel reads, padding included, on every call.
+    MatmulArgs a{n, batch, M, N, K, X, Y, A, B, C, Z, ws, false};
+    return path == SPIN_GEMM_LIMB_MFMA ? launch_matmul_limb(a, (hipStream_t)stream)
+                                       : launch_matmul_valu(a, (hipStream_t)stream);
 }
 
 spin_status spin_beaver_mul(int n, size_t count, const uint64_t *x, const uint64_t *y, const uint64_t *a,

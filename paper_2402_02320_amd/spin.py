@@ -37,6 +37,8 @@ def lib():
         L.spin_beaver_matmul.argtypes = [i32] * 5 + [p] * 6 + [i32, p, sz, p]
         L.spin_beaver_matmul_nt.argtypes = L.spin_beaver_matmul.argtypes
         L.spin_beaver_matmul_nt.restype = i32
+        L.spin_beaver_matmul_static.argtypes = [i32] * 5 + [p] * 6 + [i32, p]
+        L.spin_beaver_matmul_static.restype = i32
         L.spin_beaver_matmul_grouped.argtypes = [i32, i32, p, i32, p, sz, p]
         L.spin_beaver_matmul_grouped.restype = i32
         L.spin_beaver_matmul_grouped_workspace_bytes.argtypes = [i32, i32, p, i32]
@@ -159,6 +161,22 @@ def beaver_matmul(X, Y, A, B, C, path=LIMB_MFMA, out=None, workspace=None, y_tra
     call = lib().spin_beaver_matmul_nt if y_transposed else lib().spin_beaver_matmul
     _check(call(n, batch, M, N, K, _dev(X, "X"), _dev(Y, "Y"), _dev(A, "A"), _dev(B, "B"), _dev(C, "C"),
                 _dev(out, "Z"), path, workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
+    return out
+
+
+STATIC_WORKSPACE_BYTES = 64 << 20
+
+
+def beaver_matmul_static(X, Y, A, B, C, out, path=LIMB_MFMA):
+    """spin_beaver_matmul_static: the Beaver matmul on the library's built-in workspace.  The entry point
+    allocates nothing, so the binding does not either: the caller passes `out`."""
+    n, batch, M, K = X.shape
+    N = Y.shape[3]
+    if tuple(Y.shape) != (n, batch, K, N) or A.shape != X.shape or B.shape != Y.shape \
+            or tuple(C.shape) != (n, batch, M, N) or out.shape != C.shape:
+        raise SpinError("inconsistent operand shapes")
+    _check(lib().spin_beaver_matmul_static(n, batch, M, N, K, _dev(X, "X"), _dev(Y, "Y"), _dev(A, "A"), _dev(B, "B"),
+                                           _dev(C, "C"), _dev(out, "Z"), path, _stream()))
     return out
 
 

@@ -60,6 +60,11 @@ def test_argument_validation_needs_no_gpu(L):
     assert L.spin_trunc(2, 8, 0, fake, fake, fake, fake, fake, None) == EINVAL
     assert L.spin_trunc(2, 8, 62, fake, fake, fake, fake, fake, None) == EINVAL
     assert L.spin_trunc(2, 8, 16, fake, fake, fake, None, fake, None) == EINVAL
+    # the call on the built-in workspace refuses, before any launch, what does not fit its 64 MiB
+    st = L.spin_beaver_matmul_static
+    assert st(2, 1, 2048, 2048, 2048, fake, fake, fake, fake, fake, fake, 0, None) == EWORKSPACE
+    assert st(2, 1, 0, 8, 8, fake, fake, fake, fake, fake, fake, 0, None) == EINVAL
+    assert st(2, 1, 8, 8, 8, fake, None, fake, fake, fake, fake, 0, None) == EINVAL
     mm = L.spin_beaver_matmul
     assert mm(2, 1, 0, 4, 4, fake, fake, fake, fake, fake, fake, 0, fake, 1 << 30, None) == EINVAL
     assert mm(2, 1, 4, 4, 4, fake, fake, fake, fake, fake, fake, 7, fake, 1 << 30, None) == EINVAL
