@@ -314,6 +314,246 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
         }
 }
 
+// ------------------------------------------------- row-streaming GEMM ---
+// Z_2^64 products whose output is a single column tile (N <= 64): every left fragment would be used by
+// exactly one output tile, so writing the left operands out as fragments and reading them back (the pack
+// pre-pass) costs more HBM traffic than the product itself.  Here the left fragments never exist in
+// memory.  One workgroup owns a block of 32 rows for ALL parties (NP <= 3) and walks the inner dimension
+// once:
+//   producer wave (the last one, on a SIMD of its own)  reads the raw 32 x 32 tiles of every X_j and A_j
+//       (each exactly once), opens E = sum_j (X_j - A_j) in registers, converts E and every A_j to digits
+//       and lays them out as MFMA fragments in an LDS ring of three stages;
+//   consumer wave p (one per party, each with the whole accumulator file)  computes
+//       Z_p[32 x 64] = C_p + E . B_p' + A_p . F: per 32-deep k-tile a half step on (E, B_p') and one on
+//       (A_p, F), 72 MFMAs each.  Left fragments come from LDS; the right fragments (packed beforehand --
+//       they are small and shared by all row blocks, so they stay in L2) go straight from memory into
+//       registers, because B_p' has no second reader inside the workgroup.
+// Synchronisation: one workgroup barrier per k-tile.  In iteration g the consumers read stages g % 3
+// (A_p, first half) and (g+1) % 3 (E, second half) while the producer fills stage (g+2) % 3.
+struct RowGemmArgs {
+    const u64 *X, *A;        // [n][batch][M][K]
+    const char *packB;       // right fragment store [n+1][batch][2][KT][8][1024]: slot 0 = F, 1 + i = B_i'
+    const u64 *C;            // [n][batch][M][N]
+    u64 *Z;
+    int batch, M, N, K, KT;
+};
+
+constexpr int kRowStage = 4 * 8 * kFrag;                 // E and up to three A_j: 8 digit fragments each
+constexpr int kTurnRowBytes = 32 * 8 + 16;               // one 32-element row of the transposition buffer, padded
+constexpr int kRowLds = 3 * kRowStage + 32 * kTurnRowBytes;
+
+template <int NP>
+__global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmArgs g)
+{
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const int lane = threadIdx.x % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+    const int rblocks = (g.M + 31) / 32;
+    const int b = blockIdx.x / rblocks, rb = blockIdx.x % rblocks;
+    const int KT = g.KT;
+    const size_t mat = (size_t)g.M * g.K;
+
+    if (wave == NP) {
+        // ---------------------------------------------------------------- producer
+        // Load layout: a wave-wide load covers 4 rows x 256 bytes (lane l: row 4 i + l / 16, elements
+        // 2 (l % 16), 2 (l % 16) + 1 of the k-tile), 8 loads per 32 x 32 tile, every one made of whole
+        // 128-byte lines.  Fragment layout: lane l holds the 16 consecutive k of row l % 32, half l / 32.
+        // The tile is turned from one to the other through a wave-private LDS buffer (rows padded by 16
+        // bytes: conflict-free both ways); LDS operations of one wave execute in order, so the buffer is
+        // reused without a barrier.
+        char *turn = lds + 3 * kRowStage;
+        const int lrow = lane / 16, lk = 2 * (lane % 16);
+        const u64 *xp[NP], *ap[NP];
+        bool rok[8];
+        size_t roff[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const long row = (long)rb * 32 + 4 * i + lrow;
+            rok[i] = row < g.M;
+            roff[i] = rok[i] ? (size_t)row * g.K : 0;
+        }
+#pragma unroll
+        for (int j = 0; j < NP; ++j) {
+            xp[j] = g.X + ((size_t)j * g.batch + b) * mat;
+            ap[j] = g.A + ((size_t)j * g.batch + b) * mat;
+        }
+        u64x2 xv[NP][8], av[NP][8];
+        // Loads are unconditional: an element outside the matrix reads element 0 and is replaced by zero.
+        auto issue = [&](int j, int kt) {
+            const int k = kt * 32 + lk;
+            const bool kok = k < g.K;                    // K is even, so k + 1 < K as well
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const size_t e = (rok[i] && kok) ? roff[i] + k : 0;
+                xv[j][i] = *(const u64x2 *)(xp[j] + e);
+                av[j][i] = *(const u64x2 *)(ap[j] + e);
+            }
+        };
+        // digits of the tile held in load layout -> turn -> fragment layout -> 8 digit fragments at dst
+        auto emit = [&](const u64x2 (&t)[8], char *dst) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                u64x2 d;
+                d.x = to_digits<u64>(t[i].x);
+                d.y = to_digits<u64>(t[i].y);
+                *(u64x2 *)(turn + (4 * i + lrow) * kTurnRowBytes + (lane % 16) * 16) = d;
+            }
+            u64 w[16];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const u64x2 d = *(const u64x2 *)(turn + (lane % 32) * kTurnRowBytes + (lane / 32) * 128 + q * 16);
+                w[2 * q] = d.x;
+                w[2 * q + 1] = d.y;
+            }
+            store_digit_rows<u64>(w, dst + lane * 16);
+        };
+        auto produce = [&](int kt) {
+            char *stage = lds + (kt % 3) * kRowStage;
+            const bool kok = kt * 32 + lk < g.K;
+            const bool more = kt + 1 < KT;
+            u64x2 opened[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) opened[i] = (u64x2)(0);
+#pragma unroll
+            for (int j = 0; j < NP; ++j) {
+                u64x2 tri[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const bool ok = rok[i] && kok;
+                    tri[i] = ok ? av[j][i] : (u64x2)(0);
+                    opened[i] += ok ? xv[j][i] - av[j][i] : (u64x2)(0);
+                }
+                if (more) issue(j, kt + 1);              // refill this party's registers for the next k-tile
+                emit(tri, stage + (1 + j) * (8 * kFrag));
+            }
+            emit(opened, stage);
+        };
+#pragma unroll
+        for (int j = 0; j < NP; ++j) issue(j, 0);
+        produce(0);
+        if (KT > 1) produce(1);
+        wait_lds();
+        workgroup_barrier();
+        for (int kt = 0; kt < KT; ++kt) {
+            if (kt + 2 < KT) produce(kt + 2);
+            wait_lds();
+            workgroup_barrier();
+        }
+        return;
+    }
+
+    // -------------------------------------------------------------------- consumer
+    const int party = wave;
+    const u32 lane16 = lane * 16;
+    // Right fragments are read with buffer loads: one descriptor per operand (uniform, on the scalar unit),
+    // the lane's 16 bytes as the only vector offset, the k-tile and column block in a scalar offset, the
+    // digit as the immediate -- so the 32 loads of a k-tile need no per-lane address arithmetic.
+    const u32 cb_stride = (u32)KT * (8 * kFrag);         // from column block 0 to column block 1 (< 2^22)
+    const char *f_base = g.packB + (size_t)b * 2 * cb_stride;                            // F
+    const char *b_base = g.packB + ((size_t)(1 + party) * g.batch + b) * 2 * cb_stride;  // B_p'
+    const __amdgpu_buffer_rsrc_t f_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)f_base, 0, 2 * cb_stride, 0x00020000);
+    const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)b_base, 0, 2 * cb_stride, 0x00020000);
+    const char *e_lds = lds + lane16;
+    const char *a_lds = lds + (1 + party) * (8 * kFrag) + lane16;
+
+    v16i acc[2][8];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int d = 0; d < 8; ++d) acc[j][d] = (v16i)(0);
+    // fragment registers: [0..15] right (column block q / 8, digit q % 8), [16..23] left (digit q - 16);
+    // buffer 0 serves the (E, B_p') half step, buffer 1 the (A_p, F) half step
+    v4i fr[2][24];
+    // fragment q of k-tile offset `koff` (bytes) of a right operand / of the left fragments at `left`
+    auto fetch = [&](int q, __amdgpu_buffer_rsrc_t right, u32 koff, const char *left) -> v4i {
+        if (q < 16) {
+            const u32 soff = koff + (q / 8) * cb_stride + (q % 8 >= 4 ? 4 * kFrag : 0);
+            return (v4i)__builtin_amdgcn_raw_buffer_load_b128(right, lane16 + (q % 4) * kFrag, soff, 0);
+        }
+        return *(const v4i *)(left + (q - 16) * kFrag);
+    };
+    // One half step on buffer CUR; meanwhile the other buffer is filled for the half step that follows
+    // (FILL): the 16 right fragments from memory first, then the 8 left fragments from LDS, one after
+    // every second MFMA.  sched_barrier pins the interleave.
+    auto half_step = [&](auto cur_c, auto fill_c, __amdgpu_buffer_rsrc_t right, u32 koff, const char *left) {
+        constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1;
+        constexpr bool FILL = decltype(fill_c)::value;
+        int slot = 0;
+#pragma unroll
+        for (int da = 0; da < 8; ++da)
+#pragma unroll
+            for (int db = 0; db + da < 8; ++db)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    acc[j][da + db] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[cur][16 + da], fr[cur][8 * j + db],
+                                                                            acc[j][da + db], 0, 0, 0);
+                    if (FILL && slot % 2 == 0 && slot / 2 < 24) {
+                        fr[nxt][slot / 2] = fetch(slot / 2, right, koff, left);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    ++slot;
+                }
+    };
+    using Y = std::true_type;
+    using F = std::false_type;
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
+
+    workgroup_barrier();                                 // stages 0 and 1 are ready
+#pragma unroll
+    for (int q = 0; q < 24; ++q) fr[0][q] = fetch(q, b_rsrc, 0, e_lds);
+    u32 koff = 0;                                        // byte offset of the current k-tile in a fragment stream
+    u32 st = 0, st1 = kRowStage;                         // LDS offsets of the stages of k-tiles kt and kt + 1
+    for (int kt = 0; kt + 1 < KT; ++kt) {                // the last k-tile is peeled: no branch around MFMAs
+        half_step(B0(), Y(), f_rsrc, koff, a_lds + st);                  // E . B_p'; fills (A_p, F)
+        koff += 8 * kFrag;
+        half_step(B1(), Y(), b_rsrc, koff, e_lds + st1);                 // A_p . F; fills (E, B_p') of kt + 1
+        st = st1;
+        st1 = st1 == 2 * kRowStage ? 0 : st1 + kRowStage;
+        wait_lds();
+        workgroup_barrier();
+    }
+    koff = (u32)(KT - 1) * (8 * kFrag);                  // restated from the argument, so that it stays scalar
+    half_step(B0(), Y(), f_rsrc, koff, a_lds + st);
+    half_step(B1(), F(), b_rsrc, koff, e_lds);
+    workgroup_barrier();
+
+    // recombine the diagonals, add C_p, store (same structure as the tile kernel's epilogue)
+    const size_t zmat = (size_t)g.M * g.N;
+    const u64 *Cm = g.C + ((size_t)party * g.batch + b) * zmat;
+    u64 *Zm = g.Z + ((size_t)party * g.batch + b) * zmat;
+    const bool interior = (rb + 1) * 32 <= g.M && g.N == 64;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int col = j * 32 + lane % 32;
+        const int row0 = rb * 32 + 4 * (lane / 32);
+        auto row_of = [&](int r) { return row0 + 8 * (r / 4) + r % 4; };
+        u64 v[16];
+        __builtin_amdgcn_sched_barrier(0);
+        if (interior) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) v[r] = Cm[(size_t)row_of(r) * g.N + col];
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                v[r] = (row_of(r) < g.M && col < g.N) ? Cm[(size_t)row_of(r) * g.N + col] : 0;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+#pragma unroll
+            for (int d = 0; d < 8; ++d) v[r] += (u64)(int64_t)acc[j][d][r] << (8 * d);
+        if (interior) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Zm[(size_t)row_of(r) * g.N + col] = v[r];
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (row_of(r) < g.M && col < g.N) Zm[(size_t)row_of(r) * g.N + col] = v[r];
+        }
+    }
+}
+
 // ------------------------------------------------------------------ host ---
 struct Plan {
     int KT, nblkA, nblkB, tilesM, tilesN;
@@ -354,12 +594,61 @@ inline int choose_splits(long tiles, int steps)
     return best;
 }
 
+// Whether the row-streaming kernel takes a product: 64-bit ring, one column tile, at most three parties
+// (one consumer wave each), even K (16-byte row alignment), an inner dimension one launch may accumulate,
+// and a lower estimated cost than the tile kernel plus its pre-pass over the left operands.  Costs are in
+// k-steps of one CU (about a microsecond), the unit of choose_splits: the row kernel walks 2 KT steps per
+// block of 32 rows; the other path adds the left pack, an HBM stream of (3n + 1) operand-sized matrices at
+// about 5 MB per step-time, and one more launch.
+template <class T> inline bool rows_kernel_applies(const MatmulArgsT<T> &a, const Plan &p)
+{
+    if (!std::is_same<T, u64>::value) return false;
+    if (p.tilesN != 1 || a.n > 3 || a.K % 2 != 0 || p.KT > Ring<u64>::max_chunk_tiles) return false;
+    const int cus = compute_units();
+    const long rblocks = (long)a.batch * ceil_div(a.M, 32);
+    const double cost_rows = (double)((rblocks + cus - 1) / cus) * (2 * p.KT + 8);
+    const long tiles = (long)p.tilesM * a.n * a.batch;
+    const int sp = choose_splits(tiles, 2 * p.KT);
+    const double pack_bytes = 8.0 * (3 * a.n + 1) * a.batch * (double)a.M * a.K;
+    const double cost_tiles = (double)((tiles * sp + cus - 1) / cus) * (2 * ceil_div(p.KT, sp) + 8) + pack_bytes / 5.0e6 + 5;
+    return cost_rows <= cost_tiles;
+}
+
+inline spin_status launch_rows(const MatmulArgs &a, const Plan &p, char *packB, hipStream_t s, const char *where_pack,
+                               const char *where_gemm)
+{
+    {
+        KernelTimer timer(SPIN_KERNEL_PACK, s);
+        launch_pack_right<u64>(a, packB, p.nblkB, p.KT, s);
+        spin_status st = check_launch(where_pack);
+        if (st != SPIN_OK) return st;
+    }
+    RowGemmArgs g{a.X, a.A, packB, a.C, a.Z, a.batch, a.M, a.N, a.K, p.KT};
+    const unsigned grid = (unsigned)((long)a.batch * ceil_div(a.M, 32));
+    spin_status st = SPIN_OK;
+    for_party_count(a.n, [&](auto np) {
+        constexpr int NP = decltype(np)::value <= 3 ? decltype(np)::value : 3;   // n <= 3 is checked by the caller
+        static OncePerDevice lds_allowed;
+        auto kernel = limb_gemm_rows_kernel<NP>;
+        st = allow_dynamic_lds((const void *)kernel, kRowLds, lds_allowed);
+        if (st != SPIN_OK) return;
+        KernelTimer timer(SPIN_KERNEL_GEMM_LIMB, s);
+        kernel<<<grid, 64 * (NP + 1), kRowLds, s>>>(g);
+        st = check_launch(where_gemm);
+    });
+    return st;
+}
+
 template <class T> spin_status launch_limb(const MatmulArgsT<T> &a, hipStream_t s, const char *where_pack, const char *where_gemm)
 {
     using S = GemmShape<T>;
     const Plan p = make_plan<T>(a.n, a.batch, a.M, a.N, a.K);
     char *packA = (char *)a.workspace;
     char *packB = packA + p.packA_bytes;
+
+    if constexpr (std::is_same<T, u64>::value) {
+        if (rows_kernel_applies<T>(a, p)) return launch_rows(a, p, packB, s, where_pack, where_gemm);
+    }
 
     launch_pack<T>(a, packA, packB, p.nblkA, p.nblkB, p.KT, s);
     spin_status st = check_launch(where_pack);

@@ -334,9 +334,9 @@ __device__ inline TileId map_tile(long id, int tilesM, int tilesN, long total)
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// Launches both pack kernels of one Beaver matmul (left operands from X, A; right from Y, B).
+// Launches the pack kernels of one Beaver matmul: left operands from X, A; right operands from Y, B.
 template <class T>
-inline void launch_pack(const MatmulArgsT<T> &a, char *packA, char *packB, int nblkA, int nblkB, int KT, hipStream_t s)
+inline void launch_pack_left(const MatmulArgsT<T> &a, char *packA, int nblkA, int KT, hipStream_t s)
 {
     PackArgs<T> pa{a.X, a.A, packA, a.n, a.batch, a.M, a.K, nblkA, KT};
     constexpr int WAVES = sizeof(T) <= 8 ? 4 : 2;
@@ -344,10 +344,20 @@ inline void launch_pack(const MatmulArgsT<T> &a, char *packA, char *packB, int n
     const bool vec = a.K % EPL == 0;                     // rows 16-byte aligned
     for_party_count(a.n, [&](auto np) {
         constexpr int NP = decltype(np)::value;
-        KernelTimer timer(SPIN_KERNEL_PACK, s);
         dim3 ga((unsigned)(((long)nblkA * KT + WAVES - 1) / WAVES), 1, a.batch);
         if (vec) pack_left_kernel<NP, T, true, WAVES, false><<<ga, 64 * WAVES, 0, s>>>(pa);
         else pack_left_kernel<NP, T, false, WAVES, false><<<ga, 64 * WAVES, 0, s>>>(pa);
+    });
+}
+
+template <class T>
+inline void launch_pack_right(const MatmulArgsT<T> &a, char *packB, int nblkB, int KT, hipStream_t s)
+{
+    constexpr int WAVES = sizeof(T) <= 8 ? 4 : 2;
+    constexpr int EPL = 16 / sizeof(T);
+    const bool vec = a.K % EPL == 0;
+    for_party_count(a.n, [&](auto np) {
+        constexpr int NP = decltype(np)::value;
         if (a.y_transposed) {                            // Y, B stored [N][K]: rows of the source are fragment rows
             PackArgs<T> pb{a.Y, a.B, packB, a.n, a.batch, a.N, a.K, nblkB, KT};
             dim3 gb((unsigned)(((long)nblkB * KT + WAVES - 1) / WAVES), 1, a.batch);
@@ -359,6 +369,14 @@ inline void launch_pack(const MatmulArgsT<T> &a, char *packA, char *packB, int n
             pack_right_kernel<NP, T><<<gb, 256, 0, s>>>(pb);
         }
     });
+}
+
+template <class T>
+inline void launch_pack(const MatmulArgsT<T> &a, char *packA, char *packB, int nblkA, int nblkB, int KT, hipStream_t s)
+{
+    KernelTimer timer(SPIN_KERNEL_PACK, s);
+    launch_pack_left<T>(a, packA, nblkA, KT, s);
+    launch_pack_right<T>(a, packB, nblkB, KT, s);
 }
 
 }  // namespace

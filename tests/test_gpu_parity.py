@@ -211,6 +211,46 @@ def test_few_tiles_and_a_long_inner_dimension(n, batch, M, N, K):
     assert torch.equal(again, got)
 
 
+# Products with a single column tile (N <= 64), at most three parties and an even inner dimension take the
+# row-streaming kernel, which builds the left fragments inside the GEMM: one k-tile, two, three (the LDS ring
+# length) and many; ragged rows, columns and inner dimension; batches; in place; transposed right operand.
+ROW_SHAPES = [(3, 1, 32, 64, 32), (3, 1, 64, 64, 64), (2, 1, 33, 31, 34), (1, 1, 100, 64, 96), (3, 2, 130, 57, 46),
+              (3, 1, 1, 1, 2), (2, 3, 95, 64, 128), (3, 1, 4096, 64, 576), (3, 64, 128, 64, 128), (1, 2, 257, 33, 1000),
+              (3, 1, 8192, 64, 70), (2, 1, 9000, 48, 2048)]
+
+
+@pytest.mark.parametrize("n,batch,M,N,K", ROW_SHAPES)
+def test_beaver_matmul_single_column_tile_shapes(n, batch, M, N, K):
+    print("rows case", n, batch, M, N, K, flush=True)
+    rng = np.random.default_rng(M * 3 + K)
+    X, Y = rand_u64(rng, (n, batch, M, K)), rand_u64(rng, (n, batch, K, N))
+    A, B, C = oracle.dealer_matmul(n, batch, M, N, K, seed=M + N + K)
+    want = oracle.beaver_matmul(X, Y, A, B, C)
+    Xd, Yd, Ad, Bd, Cd = (dev(t) for t in (X, Y, A, B, C))
+    got = spin.beaver_matmul(Xd, Yd, Ad, Bd, Cd, path=spin.LIMB_MFMA)
+    assert (host(got) == want).all()
+    assert (host(Cd) == C).all()
+    Bt = dev(np.ascontiguousarray(B.transpose(0, 1, 3, 2)))
+    Yt = dev(np.ascontiguousarray(Y.transpose(0, 1, 3, 2)))
+    assert torch.equal(spin.beaver_matmul(Xd, Yt, Ad, Bt, Cd, path=spin.LIMB_MFMA, y_transposed=True), got)
+    spin.beaver_matmul(Xd, Yd, Ad, Bd, Cd, path=spin.LIMB_MFMA, out=Cd)          # in place on C
+    assert (host(Cd) == want).all()
+
+
+def test_single_column_tile_worst_case_digits():
+    # all digits -128 in every operand of both products, at the longest inner dimension the row kernel accumulates
+    # in one launch (511 k-tiles): the int32 partial sums run at their proven extreme
+    n, M, N, K = 2, 300, 64, 511 * 32
+    worst = np.uint64(0x7F7F7F7F7F7F7F80)
+    X = np.zeros((n, 1, M, K), dtype=np.uint64); X[:] = worst
+    Y = np.zeros((n, 1, K, N), dtype=np.uint64); Y[:] = worst
+    A = np.zeros_like(X); B = np.zeros_like(Y); A[1] = worst; B[1] = worst
+    C = np.zeros((n, 1, M, N), dtype=np.uint64)
+    want = oracle.beaver_matmul(X, Y, A, B, C)
+    got = spin.beaver_matmul(dev(X), dev(Y), dev(A), dev(B), dev(C), path=spin.LIMB_MFMA)
+    assert (host(got) == want).all()
+
+
 def test_limb_path_worst_case_digits_and_inner_dimension_split():
     # every digit of every operand equal to -128 (value 0x7F7F7F7F7F7F7F80), with K large enough that
     # the inner dimension is split into more than one accumulation chunk: the int32 partial sums run
