@@ -319,17 +319,23 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
 // exactly one output tile, so writing the left operands out as fragments and reading them back (the pack
 // pre-pass) costs more HBM traffic than the product itself.  Here the left fragments never exist in
 // memory.  One workgroup owns a block of 32 rows for ALL parties (NP <= 3) and walks the inner dimension
-// once:
-//   producer wave (the last one, on a SIMD of its own)  reads the raw 32 x 32 tiles of every X_j and A_j
-//       (each exactly once), opens E = sum_j (X_j - A_j) in registers, converts E and every A_j to digits
-//       and lays them out as MFMA fragments in an LDS ring of three stages;
+// once; the raw 32 x 32 tiles of every X_j and A_j go memory -> LDS exactly once (direct-to-LDS loads,
+// no register is held while they fly).
+//   producer wave (the last one, on a SIMD of its own)  issues those loads one k-tile ahead, opens
+//       E = sum_j (X_j - A_j) from the raw tiles, converts E to digits and lays it out as MFMA fragments
+//       in a two-stage LDS ring;
 //   consumer wave p (one per party, each with the whole accumulator file)  computes
-//       Z_p[32 x 64] = C_p + E . B_p' + A_p . F: per 32-deep k-tile a half step on (E, B_p') and one on
-//       (A_p, F), 72 MFMAs each.  Left fragments come from LDS; the right fragments (packed beforehand --
-//       they are small and shared by all row blocks, so they stay in L2) go straight from memory into
-//       registers, because B_p' has no second reader inside the workgroup.
-// Synchronisation: one workgroup barrier per k-tile.  In iteration g the consumers read stages g % 3
-// (A_p, first half) and (g+1) % 3 (E, second half) while the producer fills stage (g+2) % 3.
+//       Z_p[32 x 64] = C_p + A_p . F + E . B_p': per 32-deep k-tile a half step on (A_p, F) and one on
+//       (E, B_p'), 72 MFMAs each.  It converts its own A_p from the raw tile in registers (the vector ALU is
+//       idle under the MFMAs) and reads the right fragments (packed beforehand: they are small, shared by
+//       all row blocks and stay in L2) straight from memory into registers, because B_p' has no second
+//       reader inside the workgroup.
+// Nothing is masked at ragged edges: loads that would leave the matrix are redirected to the tile's first
+// element, and what they bring only meets zero-padded rows of the right fragments (k >= K) or lands in
+// output rows that are never stored (row >= M).
+// Synchronisation: one workgroup barrier per k-tile.  In iteration g the consumers read E(g) from ring
+// stage g % 2 (first half) and raw A_p(g+1) from raw slot (g+1) % 2 (second half); the producer reads raw
+// slot (g+1) % 2, writes E(g+1) to stage (g+1) % 2 and refills raw slot g % 2 with k-tile g + 2.
 struct RowGemmArgs {
     const u64 *X, *A;        // [n][batch][M][K]
     const char *packB;       // right fragment store [n+1][batch][2][KT][8][1024]: slot 0 = F, 1 + i = B_i'
@@ -338,9 +344,48 @@ struct RowGemmArgs {
     int batch, M, N, K, KT;
 };
 
-constexpr int kRowStage = 4 * 8 * kFrag;                 // E and up to three A_j: 8 digit fragments each
-constexpr int kTurnRowBytes = 32 * 8 + 16;               // one 32-element row of the transposition buffer, padded
-constexpr int kRowLds = 3 * kRowStage + 32 * kTurnRowBytes;
+// Raw tile in LDS: 64 groups of 128 bytes, group 2 r + h = the 16 consecutive k (8 pieces of 16 bytes) of
+// row r, half h; piece q sits at position q ^ (r & 7) of its group, so that the 8 lanes that read the same
+// piece of 8 consecutive rows hit 8 different bank groups.  A direct-to-LDS load fills 1 KiB = 8 groups =
+// 4 rows x 256 bytes with whole 128-byte lines of memory.
+constexpr int kRawTile = 32 * 32 * 8;
+constexpr int kRawSlot = 3 * 2 * kRawTile;               // X_j then A_j for up to three parties
+constexpr int kRowLds = 2 * kRawSlot + 2 * 8 * kFrag;    // two raw slots, two stages of E fragments
+
+// 16 direct-to-LDS loads: the 8 chunks of X_j's and A_j's raw tile.  m0 (LDS base of each load) is put
+// back afterwards; the scalar add that sets it clobbers scc.
+__device__ inline void load_raw_pair(const char *xs, const char *as, u32 lds_dst, const u32 (&voff)[8])
+{
+    u32 saved_m0;
+    asm volatile(
+        "s_mov_b32 %0, m0\n\t"
+        "s_add_u32 m0, %3, 0x0000\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %4, %1\n\t"
+        "s_add_u32 m0, %3, 0x2000\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %4, %2\n\t"
+        "s_add_u32 m0, %3, 0x0400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %5, %1\n\t"
+        "s_add_u32 m0, %3, 0x2400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %5, %2\n\t"
+        "s_add_u32 m0, %3, 0x0800\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %6, %1\n\t"
+        "s_add_u32 m0, %3, 0x2800\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %6, %2\n\t"
+        "s_add_u32 m0, %3, 0x0c00\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %7, %1\n\t"
+        "s_add_u32 m0, %3, 0x2c00\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %7, %2\n\t"
+        "s_add_u32 m0, %3, 0x1000\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %8, %1\n\t"
+        "s_add_u32 m0, %3, 0x3000\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %8, %2\n\t"
+        "s_add_u32 m0, %3, 0x1400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %9, %1\n\t"
+        "s_add_u32 m0, %3, 0x3400\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %9, %2\n\t"
+        "s_add_u32 m0, %3, 0x1800\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %10, %1\n\t"
+        "s_add_u32 m0, %3, 0x3800\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %10, %2\n\t"
+        "s_add_u32 m0, %3, 0x1c00\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %11, %1\n\t"
+        "s_add_u32 m0, %3, 0x3c00\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %11, %2\n\t"
+        "s_mov_b32 m0, %0"
+        : "=&s"(saved_m0)
+        : "s"(xs), "s"(as), "s"(lds_dst), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "v"(voff[4]),
+          "v"(voff[5]), "v"(voff[6]), "v"(voff[7])
+        : "memory", "scc");
+}
+static_assert(kRawTile == 0x2000, "load_raw_pair hard-codes the raw tile size");
+
+typedef __attribute__((address_space(3))) char lds_char;
+typedef __attribute__((address_space(3))) const u64x2 lds_u64x2;
+typedef __attribute__((address_space(3))) const v4i lds_v4i;
 
 template <int NP>
 __global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmArgs g)
@@ -351,91 +396,73 @@ __global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmAr
     const int rblocks = (g.M + 31) / 32;
     const int b = blockIdx.x / rblocks, rb = blockIdx.x % rblocks;
     const int KT = g.KT;
-    const size_t mat = (size_t)g.M * g.K;
+    lds_char *lds3 = (lds_char *)lds;
+    lds_char *e_ring = lds3 + 2 * kRawSlot;
+    // this lane's 16 consecutive k of row lane % 32, half lane / 32, in a raw tile: piece q at raw_lane ^ (16 q)
+    const u32 raw_lane = (2 * (lane % 32) + lane / 32) * 128 + (lane % 8) * 16;
 
     if (wave == NP) {
         // ---------------------------------------------------------------- producer
-        // Load layout: a wave-wide load covers 4 rows x 256 bytes (lane l: row 4 i + l / 16, elements
-        // 2 (l % 16), 2 (l % 16) + 1 of the k-tile), 8 loads per 32 x 32 tile, every one made of whole
-        // 128-byte lines.  Fragment layout: lane l holds the 16 consecutive k of row l % 32, half l / 32.
-        // The tile is turned from one to the other through a wave-private LDS buffer (rows padded by 16
-        // bytes: conflict-free both ways); LDS operations of one wave execute in order, so the buffer is
-        // reused without a barrier.
-        char *turn = lds + 3 * kRowStage;
-        const int lrow = lane / 16, lk = 2 * (lane % 16);
-        const u64 *xp[NP], *ap[NP];
-        bool rok[8];
-        size_t roff[8];
+        // load i, lane p: group 8 i + p / 8 -> row 4 i + p / 16, half (p / 8) % 2; position p % 8 holds piece
+        // (p % 8) ^ (row & 7); the lane fetches that piece of the row's 256 bytes
+        const size_t row_pitch = (size_t)g.K * 8;
+        const bool k_edge = KT * 32 > g.K;               // the last k-tile is ragged
+        u32 voff[8], voff_last[8];                       // per-lane byte offsets from the tile's first element
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const long row = (long)rb * 32 + 4 * i + lrow;
-            rok[i] = row < g.M;
-            roff[i] = rok[i] ? (size_t)row * g.K : 0;
+            const int row = 4 * i + lane / 16, half = (lane / 8) % 2, piece = (lane % 8) ^ (row & 7);
+            const u32 off = (u32)(row * row_pitch) + half * 128 + piece * 16;     // K <= 16352: far below 2^32
+            const bool row_ok = rb * 32 + row < g.M;
+            const bool k_ok = (KT - 1) * 32 + 16 * half + 2 * piece < g.K;        // K is even
+            voff[i] = row_ok ? off : 0;
+            voff_last[i] = row_ok && k_ok ? off : 0;
         }
+        const size_t tile0 = ((size_t)b * g.M + (size_t)rb * 32) * row_pitch;     // party 0, k-tile 0
+        const size_t party_stride = (size_t)g.batch * g.M * row_pitch;
+        const u32 raw0 = (u32)(uintptr_t)lds3;
+        auto issue = [&](int kt) {                       // all parties' tiles of k-tile kt -> raw slot kt % 2
+            const u32 dst = raw0 + (kt % 2) * kRawSlot;
+            const bool last = k_edge && kt + 1 == KT;
 #pragma unroll
-        for (int j = 0; j < NP; ++j) {
-            xp[j] = g.X + ((size_t)j * g.batch + b) * mat;
-            ap[j] = g.A + ((size_t)j * g.batch + b) * mat;
-        }
-        u64x2 xv[NP][8], av[NP][8];
-        // Loads are unconditional: an element outside the matrix reads element 0 and is replaced by zero.
-        auto issue = [&](int j, int kt) {
-            const int k = kt * 32 + lk;
-            const bool kok = k < g.K;                    // K is even, so k + 1 < K as well
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const size_t e = (rok[i] && kok) ? roff[i] + k : 0;
-                xv[j][i] = *(const u64x2 *)(xp[j] + e);
-                av[j][i] = *(const u64x2 *)(ap[j] + e);
+            for (int j = 0; j < NP; ++j) {
+                const size_t off = tile0 + j * party_stride + (size_t)kt * 256;
+                if (last) load_raw_pair((const char *)g.X + off, (const char *)g.A + off, dst + j * (2 * kRawTile), voff_last);
+                else load_raw_pair((const char *)g.X + off, (const char *)g.A + off, dst + j * (2 * kRawTile), voff);
             }
         };
-        // digits of the tile held in load layout -> turn -> fragment layout -> 8 digit fragments at dst
-        auto emit = [&](const u64x2 (&t)[8], char *dst) {
+        auto open_tile = [&](int kt) {                   // E(kt) from raw slot kt % 2 -> fragment stage kt % 2
+            lds_char *slot = lds3 + (kt % 2) * kRawSlot;
+            u64x2 opened[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                u64x2 d;
-                d.x = to_digits<u64>(t[i].x);
-                d.y = to_digits<u64>(t[i].y);
-                *(u64x2 *)(turn + (4 * i + lrow) * kTurnRowBytes + (lane % 16) * 16) = d;
-            }
+            for (int q = 0; q < 8; ++q) opened[q] = (u64x2)(0);
+#pragma unroll
+            for (int j = 0; j < NP; ++j)
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const u64x2 xv = *(lds_u64x2 *)(slot + j * (2 * kRawTile) + (raw_lane ^ (16 * q)));
+                    const u64x2 av = *(lds_u64x2 *)(slot + j * (2 * kRawTile) + kRawTile + (raw_lane ^ (16 * q)));
+                    opened[q] += xv - av;
+                }
             u64 w[16];
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                const u64x2 d = *(const u64x2 *)(turn + (lane % 32) * kTurnRowBytes + (lane / 32) * 128 + q * 16);
-                w[2 * q] = d.x;
-                w[2 * q + 1] = d.y;
+                w[2 * q] = to_digits<u64>(opened[q].x);
+                w[2 * q + 1] = to_digits<u64>(opened[q].y);
             }
-            store_digit_rows<u64>(w, dst + lane * 16);
+            store_digit_rows<u64>(w, lds + 2 * kRawSlot + (kt % 2) * (8 * kFrag) + lane * 16);
         };
-        auto produce = [&](int kt) {
-            char *stage = lds + (kt % 3) * kRowStage;
-            const bool kok = kt * 32 + lk < g.K;
-            const bool more = kt + 1 < KT;
-            u64x2 opened[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) opened[i] = (u64x2)(0);
-#pragma unroll
-            for (int j = 0; j < NP; ++j) {
-                u64x2 tri[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const bool ok = rok[i] && kok;
-                    tri[i] = ok ? av[j][i] : (u64x2)(0);
-                    opened[i] += ok ? xv[j][i] - av[j][i] : (u64x2)(0);
-                }
-                if (more) issue(j, kt + 1);              // refill this party's registers for the next k-tile
-                emit(tri, stage + (1 + j) * (8 * kFrag));
-            }
-            emit(opened, stage);
-        };
-#pragma unroll
-        for (int j = 0; j < NP; ++j) issue(j, 0);
-        produce(0);
-        if (KT > 1) produce(1);
+        issue(0);
+        wait_loads<0>();
+        if (KT > 1) issue(1);
+        open_tile(0);
+        wait_loads<0>();
         wait_lds();
-        workgroup_barrier();
+        workgroup_barrier();                             // raw tiles 0 and 1 and E(0) are in LDS
+        workgroup_barrier();                             // the consumers have taken A_p(0) out of raw slot 0
         for (int kt = 0; kt < KT; ++kt) {
-            if (kt + 2 < KT) produce(kt + 2);
+            if (kt + 2 < KT) issue(kt + 2);
+            if (kt + 1 < KT) open_tile(kt + 1);
+            wait_loads<0>();
             wait_lds();
             workgroup_barrier();
         }
@@ -453,8 +480,7 @@ __global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmAr
     const char *b_base = g.packB + ((size_t)(1 + party) * g.batch + b) * 2 * cb_stride;  // B_p'
     const __amdgpu_buffer_rsrc_t f_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)f_base, 0, 2 * cb_stride, 0x00020000);
     const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)b_base, 0, 2 * cb_stride, 0x00020000);
-    const char *e_lds = lds + lane16;
-    const char *a_lds = lds + (1 + party) * (8 * kFrag) + lane16;
+    lds_char *a_raw = lds3 + party * (2 * kRawTile) + kRawTile;      // raw A_p in raw slot 0
 
     v16i acc[2][8];
 #pragma unroll
@@ -464,18 +490,51 @@ __global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmAr
     // fragment registers: [0..15] right (column block q / 8, digit q % 8), [16..23] left (digit q - 16);
     // buffer 0 serves the (E, B_p') half step, buffer 1 the (A_p, F) half step
     v4i fr[2][24];
-    // fragment q of k-tile offset `koff` (bytes) of a right operand / of the left fragments at `left`
-    auto fetch = [&](int q, __amdgpu_buffer_rsrc_t right, u32 koff, const char *left) -> v4i {
-        if (q < 16) {
-            const u32 soff = koff + (q / 8) * cb_stride + (q % 8 >= 4 ? 4 * kFrag : 0);
-            return (v4i)__builtin_amdgcn_raw_buffer_load_b128(right, lane16 + (q % 4) * kFrag, soff, 0);
-        }
-        return *(const v4i *)(left + (q - 16) * kFrag);
+    auto right_fragment = [&](int q, __amdgpu_buffer_rsrc_t rsrc, u32 koff) -> v4i {
+        const u32 soff = koff + (q / 8) * cb_stride + (q % 8 >= 4 ? 4 * kFrag : 0);
+        return (v4i)__builtin_amdgcn_raw_buffer_load_b128(rsrc, lane16 + (q % 4) * kFrag, soff, 0);
     };
-    // One half step on buffer CUR; meanwhile the other buffer is filled for the half step that follows
-    // (FILL): the 16 right fragments from memory first, then the 8 left fragments from LDS, one after
-    // every second MFMA.  sched_barrier pins the interleave.
-    auto half_step = [&](auto cur_c, auto fill_c, __amdgpu_buffer_rsrc_t right, u32 koff, const char *left) {
+    // A_p from the raw tile to the eight left fragments of buffer 1, a quarter (elements 4 c .. 4 c + 3 of this
+    // lane's 16 = pieces 2 c, 2 c + 1 -> component c of every fragment) at a time, in steps small enough to
+    // sit between two MFMAs without holding the matrix pipe up:
+    //   step 0  read the two pieces from LDS          step 1, 2  balanced digits of elements 0, 1 / 2, 3
+    //   step 3..6  the 4 x 4 byte transposes of the low / high words: first level, second level
+    u64x2 piece[2];
+    u64 dig[4];
+    u32 half_t[4];
+    auto convert_step = [&](int c, int step, lds_char *tile) {
+        if (step == 0) {
+            piece[0] = *(lds_u64x2 *)(tile + (raw_lane ^ (32 * c)));
+            piece[1] = *(lds_u64x2 *)(tile + (raw_lane ^ (32 * c + 16)));
+        } else if (step == 1) {
+            dig[0] = to_digits<u64>(piece[0].x);
+            dig[1] = to_digits<u64>(piece[0].y);
+        } else if (step == 2) {
+            dig[2] = to_digits<u64>(piece[1].x);
+            dig[3] = to_digits<u64>(piece[1].y);
+        } else {
+            const int word = (step - 3) / 2;
+            if ((step - 3) % 2 == 0) {
+                const u32 a0 = (u32)(dig[0] >> (32 * word)), a1 = (u32)(dig[1] >> (32 * word));
+                const u32 a2 = (u32)(dig[2] >> (32 * word)), a3 = (u32)(dig[3] >> (32 * word));
+                half_t[0] = __builtin_amdgcn_perm(a1, a0, 0x05010400u);
+                half_t[1] = __builtin_amdgcn_perm(a1, a0, 0x07030602u);
+                half_t[2] = __builtin_amdgcn_perm(a3, a2, 0x05010400u);
+                half_t[3] = __builtin_amdgcn_perm(a3, a2, 0x07030602u);
+            } else {
+                fr[1][16 + 4 * word + 0][c] = (int)__builtin_amdgcn_perm(half_t[2], half_t[0], 0x05040100u);
+                fr[1][16 + 4 * word + 1][c] = (int)__builtin_amdgcn_perm(half_t[2], half_t[0], 0x07060302u);
+                fr[1][16 + 4 * word + 2][c] = (int)__builtin_amdgcn_perm(half_t[3], half_t[1], 0x05040100u);
+                fr[1][16 + 4 * word + 3][c] = (int)__builtin_amdgcn_perm(half_t[3], half_t[1], 0x07060302u);
+            }
+        }
+    };
+    // One half step of 72 MFMAs on buffer CUR; between them the other buffer is filled for the half step
+    // that follows.  After the even MFMAs 0, 2, .. 30: its 16 right fragments (memory).  Its left fragments:
+    // E from the fragment ring (8 LDS reads after the even MFMAs 32 .. 46, CUR = 1), or A_p converted from the
+    // raw tile (CUR = 0): conversion step m = 0 .. 25 after the odd MFMA 2 m + 1, quarter c reading at
+    // m = 6 c - 1 (0 for c = 0) and working at m = 6 c + 2 .. 6 c + 7.  sched_barrier pins the interleave.
+    auto half_step = [&](auto cur_c, auto fill_c, __amdgpu_buffer_rsrc_t rsrc, u32 koff, lds_char *left) {
         constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1;
         constexpr bool FILL = decltype(fill_c)::value;
         int slot = 0;
@@ -487,9 +546,22 @@ __global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmAr
                 for (int j = 0; j < 2; ++j) {
                     acc[j][da + db] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fr[cur][16 + da], fr[cur][8 * j + db],
                                                                             acc[j][da + db], 0, 0, 0);
-                    if (FILL && slot % 2 == 0 && slot / 2 < 24) {
-                        fr[nxt][slot / 2] = fetch(slot / 2, right, koff, left);
-                        __builtin_amdgcn_sched_barrier(0);
+                    if (FILL && slot % 2 == 0) {
+                        const int item = slot / 2;
+                        if (item < 16) {
+                            fr[nxt][item] = right_fragment(item, rsrc, koff);
+                            __builtin_amdgcn_sched_barrier(0);
+                        } else if (cur == 1 && item < 24) {
+                            fr[0][item] = *(lds_v4i *)(left + lane16 + (item - 16) * kFrag);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+                    if (FILL && cur == 0 && slot % 2 == 1) {
+                        const int m = slot / 2;
+                        if (m == 0) convert_step(0, 0, left);
+                        if (m >= 5 && m <= 17 && (m + 1) % 6 == 0) convert_step((m + 1) / 6, 0, left);
+                        if (m >= 2 && m <= 25) convert_step((m - 2) / 6, 1 + (m - 2) % 6, left);
+                        if (m <= 25) __builtin_amdgcn_sched_barrier(0);
                     }
                     ++slot;
                 }
@@ -499,23 +571,28 @@ __global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmAr
     using B0 = std::integral_constant<int, 0>;
     using B1 = std::integral_constant<int, 1>;
 
-    workgroup_barrier();                                 // stages 0 and 1 are ready
+    workgroup_barrier();                                 // raw tiles 0 and 1 and E(0) are in LDS
 #pragma unroll
-    for (int q = 0; q < 24; ++q) fr[0][q] = fetch(q, b_rsrc, 0, e_lds);
+    for (int q = 0; q < 16; ++q) fr[1][q] = right_fragment(q, f_rsrc, 0);
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int step = 0; step < 7; ++step) convert_step(c, step, a_raw);
+    wait_lds();
+    workgroup_barrier();                                 // raw slot 0 may be refilled
     u32 koff = 0;                                        // byte offset of the current k-tile in a fragment stream
-    u32 st = 0, st1 = kRowStage;                         // LDS offsets of the stages of k-tiles kt and kt + 1
+    u32 par = 0;                                         // kt % 2
     for (int kt = 0; kt + 1 < KT; ++kt) {                // the last k-tile is peeled: no branch around MFMAs
-        half_step(B0(), Y(), f_rsrc, koff, a_lds + st);                  // E . B_p'; fills (A_p, F)
+        half_step(B1(), Y(), b_rsrc, koff, e_ring + par * (8 * kFrag));                // A_p . F; fills (E, B_p') of kt
         koff += 8 * kFrag;
-        half_step(B1(), Y(), b_rsrc, koff, e_lds + st1);                 // A_p . F; fills (E, B_p') of kt + 1
-        st = st1;
-        st1 = st1 == 2 * kRowStage ? 0 : st1 + kRowStage;
+        par ^= 1;
+        half_step(B0(), Y(), f_rsrc, koff, a_raw + par * kRawSlot);                    // E . B_p'; fills (A_p, F) of kt + 1
         wait_lds();
         workgroup_barrier();
     }
     koff = (u32)(KT - 1) * (8 * kFrag);                  // restated from the argument, so that it stays scalar
-    half_step(B0(), Y(), f_rsrc, koff, a_lds + st);
-    half_step(B1(), F(), b_rsrc, koff, e_lds);
+    half_step(B1(), Y(), b_rsrc, koff, e_ring + ((KT - 1) % 2) * (8 * kFrag));
+    half_step(B0(), F(), f_rsrc, koff, a_raw);
     workgroup_barrier();
 
     // recombine the diagonals, add C_p, store (same structure as the tile kernel's epilogue)
