@@ -1,15 +1,22 @@
 #!/usr/bin/env python3
 """Benchmark of the Beaver-multiplication hot path on one MI355X.
 
-One step = one pass of the whole path over one batch of synthetic input:
-share X and Y -> Beaver matmul (open E, F; share update) -> truncate ->
-elementwise Beaver mul of the result with a second shared tensor -> truncate.
+One step = one pass of the whole path over one batch of synthetic input, every
+leg the configuration names:
+  configs 1, 3, 5  share X, Y -> Beaver matmul (open E, F; share update) -> trunc ->
+                   elementwise Beaver mul of the result with a shared tensor -> trunc
+  config 2         the same on the 1024^3 product, then share + elementwise Beaver
+                   mul + trunc on the 2^24-element vectors
+  config 4         Q.K^T (key matrix stored transposed, spin_beaver_matmul_nt) -> trunc ->
+                   elementwise Beaver mul over the 8x8x128x128 scores -> trunc -> P.V -> trunc
 Default workload: configuration 5 (5 parties, 4096^3, f = 16), the headline
-configuration; all inputs are resident in HBM before the timed region.
+configuration; --config all prints one line per configuration.  All inputs are
+resident in HBM before the timed region.
 
-Prints ONE JSON line (metric: Z_2^64 ring MACs/s of the Beaver matmul, counted
-as n*2*batch*M*N*K per step), with the roofline of the dominant kernel and the
-CPU oracle timed on the host cores.
+Prints ONE JSON line per configuration (metric: Z_2^64 ring MACs/s of the Beaver
+matmuls, counted as n*2*batch*M*N*K per product), with the roofline of the
+dominant kernel and the CPU oracle timed on the host cores; the oracle's rows
+are also compared with the Z the timed steps left behind.
 """
 import argparse
 import json
@@ -32,7 +39,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--config", default="5", choices=["1", "2", "3", "4", "5", "all"],
+                    help="benchmark configuration (default 5, the headline); all: one JSON line per configuration")
     ap.add_argument("--path", default="limb", choices=["limb", "valu"])
     ap.add_argument("--workload", default="matmul", choices=["matmul", "poly", "matmul128", "matmul32"],
                     help="matmul: the Beaver-matmul hot path (the benchmark); poly: completed-square polynomial "
@@ -43,7 +51,10 @@ def parse():
                          "configurations; the per-kernel figures then come from a separate eager pass)")
     ap.add_argument("--fuse-mul-trunc", action="store_true",
                     help="run the elementwise multiplication and its truncation as the one-pass spin_beaver_mul_trunc")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true",
+                    help="skip the oracle leg (and with it the check of the timed Z against the oracle)")
+    ap.add_argument("--no-mfma-ceiling", dest="mfma_ceiling", action="store_false",
+                    help="skip the register-only MFMA rate probe that follows the timed steps")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -92,43 +103,52 @@ def mfma_ceiling(kernel_tops):
     return res
 
 
-def cpu_baseline(cfg, target_s):
-    """The oracle, as it stands, on a bounded row sample of the same workload."""
+def cpu_baseline(cfg, target_s, gpu_rows_of_z=None):
+    """The oracle, as it stands, on a bounded row sample of the first GEMM of the configuration: seeded inputs and the
+    dealer's triple from oracle/ alone, timed on all host cores.  gpu_rows_of_z(rows) returns the same rows of the Z
+    the timed GPU steps produced; they must equal the oracle's word for word."""
     import oracle
     from paper_2402_02320_amd import workloads
     c = workloads.CONFIGS[cfg]
-    g = c.gemms[0]
     Xr, Yr = workloads.gemm_plaintexts(cfg)
     batch, M, K = Xr.shape
     N = Yr.shape[2]
     X = oracle.share(oracle.encode(Xr, c.f), c.n, c.seed, oracle.STREAM_X)
     Y = oracle.share(oracle.encode(Yr, c.f), c.n, c.seed, oracle.STREAM_Y)
-    A = np.stack([oracle.random(batch * M * K, c.seed, oracle.STREAM_A, i).reshape(batch, M, K) for i in range(c.n)])
-    B = np.stack([oracle.random(batch * K * N, c.seed, oracle.STREAM_B, i).reshape(batch, K, N) for i in range(c.n)])
-    C = np.stack([oracle.random(batch * M * N, c.seed, oracle.STREAM_C, i).reshape(batch, M, N) for i in range(c.n)])
+    A, B, C = oracle.dealer_matmul(c.n, batch, M, N, K, seed=c.seed)        # untimed: the offline phase
     threads = oracle.threads()
 
-    def run(nrows):
-        rows = np.linspace(0, M - 1, nrows).astype(np.int32)
+    def run(rows):
         t0 = time.perf_counter()
-        oracle.beaver_matmul(X, Y, A, B, C, rows=rows)
-        return time.perf_counter() - t0
+        z = oracle.beaver_matmul(X, Y, A, B, C, rows=rows)
+        return time.perf_counter() - t0, z
+
+    def spread(nrows):
+        return np.unique(np.linspace(0, M - 1, nrows).astype(np.int32))
     probe_rows = min(M, 2 * threads)
-    t_probe = run(probe_rows)
+    t_probe, _ = run(spread(probe_rows))
     # the opening of E and F is paid once per call whatever the row count; estimate it from a second probe
-    t_probe2 = run(min(M, 4 * threads))
+    t_probe2, _ = run(spread(min(M, 4 * threads)))
     per_row = max((t_probe2 - t_probe) / max(1, min(M, 4 * threads) - probe_rows), 1e-9)
     nrows = int(max(probe_rows, min(M, (target_s - max(t_probe - per_row * probe_rows, 0.0)) / per_row)))
-    nrows = max(threads, nrows // threads * threads)
-    t = run(nrows)
+    nrows = min(M, max(threads, nrows // threads * threads))
+    rows = spread(nrows)
+    nrows = int(rows.size)
+    t, z_rows = run(rows)
+    checked = None
+    if gpu_rows_of_z is not None:
+        got = gpu_rows_of_z(rows)
+        if got.shape != z_rows.shape or not (got == z_rows).all():
+            raise SystemExit("bench.py: the Z the timed GPU steps produced differs from the oracle on the sampled rows")
+        checked = nrows * batch
     macs = (2 * c.n + 1) * batch * nrows * N * K     # the oracle also forms E.F explicitly for party 0
     credited = 2 * c.n * batch * nrows * N * K
     # per-core figure: the row loop alone on one thread (the opening is subtracted through a second run)
     oracle.set_threads(1)
     r1 = max(1, nrows // (4 * threads))
-    t_a, t_b = run(r1), run(2 * r1)
+    (t_a, _), (t_b, _) = run(spread(r1)), run(spread(min(M, 2 * r1)))
     oracle.set_threads(threads)
-    one_core = 2 * c.n * batch * r1 * N * K / max(t_b - t_a, 1e-9)
+    one_core = 2 * c.n * batch * max(1, min(M, 2 * r1) - r1) * N * K / max(t_b - t_a, 1e-9)
     model = ""
     try:
         for line in open("/proc/cpuinfo"):
@@ -137,11 +157,13 @@ def cpu_baseline(cfg, target_s):
                 break
     except OSError:
         pass
-    return {"value": credited / t, "unit": "ring MAC/s", "cores": threads, "cpu_model": model, "kind": "oracle",
-            "sample": "config %d, %d of %d output rows of every party's share (%.1f s, incl. opening E and F; "
-                      "%.3g ring MACs executed, %.3g credited as n*2*rows*N*K)" % (cfg, nrows, M, t, macs, credited),
-            "one_core_value": one_core,
-            "one_core_sample": "row loop on 1 thread: time of %d rows minus time of %d rows" % (2 * r1, r1)}
+    res = {"value": credited / t, "unit": "ring MAC/s", "cores": threads, "cpu_model": model, "kind": "oracle",
+           "sample": "config %d, first GEMM, %d of %d output rows (x %d batch entries) of every party's share (%.1f s, "
+                     "incl. opening E and F; %.3g ring MACs executed, %.3g credited as n*2*rows*N*K)"
+                     % (cfg, nrows, M, batch, t, macs, credited),
+           "one_core_value": one_core,
+           "one_core_sample": "row loop on 1 thread: time of %d rows minus time of %d rows" % (min(M, 2 * r1), r1)}
+    return res, checked
 
 
 def bench_poly(args):
@@ -252,88 +274,156 @@ def bench_matmul_other_ring(args, bits):
                       "roofline": roof, "gemm_avg_ms": gemm_ms, "pack_avg_ms": pk / pc if pc else None}))
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (all parties' shares live on one MI355X); "
-              "run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def run_config(args, cfg):
+    """Times the hot path on one configuration and returns the JSON record."""
     import torch
     from paper_2402_02320_amd import spin, workloads
-    if not os.path.exists(spin.LIB_PATH):
-        from paper_2402_02320_amd import build
-        build.build()
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    torch.cuda.set_device(0)
-    if args.workload == "poly":
-        return bench_poly(args)
-    if args.workload in ("matmul128", "matmul32"):
-        return bench_matmul_other_ring(args, 128 if args.workload == "matmul128" else 32)
-    c = workloads.CONFIGS[args.config]
-    g = c.gemms[0]
+    c = workloads.CONFIGS[cfg]
     n, f = c.n, c.f
     path = spin.LIMB_MFMA if args.path == "limb" else spin.VALU
     S = {"X": 1, "Y": 2, "A": 3, "B": 4, "C": 5, "R": 6, "RT": 7, "RM": 8, "W": 9}
+    alg_bytes = {}                 # algorithmic bytes per step of the HBM-bound kernel classes
 
-    # ---- untimed setup: plaintexts, triples and truncation tuples, all resident in HBM -------------
-    Xr, Yr = workloads.gemm_plaintexts(args.config)
-    batch, M, K = Xr.shape
-    N = Yr.shape[2]
-    x = spin.encode(torch.from_numpy(Xr).cuda(), f)
-    y = spin.encode(torch.from_numpy(Yr).cuda(), f)
-    del Xr, Yr
-    szA, szB, szC = batch * M * K, batch * K * N, batch * M * N
+    def count_bytes(kernel, nbytes):
+        alg_bytes[kernel] = alg_bytes.get(kernel, 0.0) + nbytes
 
-    def party_random(count, stream, shape):
-        return torch.stack([spin.random(count, c.seed, stream, i) for i in range(n)]).view((n,) + shape)
-    A = party_random(szA, S["A"], (batch, M, K))
-    B = party_random(szB, S["B"], (batch, K, N))
-    ws_bytes = spin.beaver_matmul_workspace_bytes(n, batch, M, N, K, path)
-    # dealer: C = (sum A_i).(sum B_i) through the library's own ring GEMM (one party, zero triple), then shared.
-    # It runs on the VALU path so that every limb_gemm_kernel launch a profiler sees belongs to the workload.
-    ws1 = torch.empty(spin.beaver_matmul_workspace_bytes(1, batch, M, N, K, spin.VALU), dtype=torch.uint8,
-                      device="cuda")
-    a_open, b_open = spin.open(A)[None], spin.open(B)[None]
-    zA, zB, zC = torch.zeros_like(a_open), torch.zeros_like(b_open), torch.zeros((1, batch, M, N), dtype=torch.int64,
-                                                                                device="cuda")
-    c_plain = spin.beaver_matmul(a_open, b_open, zA, zB, zC, path=spin.VALU, workspace=ws1)
-    C = spin.share(c_plain[0], n, c.seed, S["C"])
-    del a_open, b_open, zA, zB, zC, c_plain, ws1
+    def party_random(count, stream, shape, seed):
+        return torch.stack([spin.random(count, seed, stream, i) for i in range(n)]).view((n,) + shape)
 
-    def trunc_tuple(count, salt):
-        r_sh = torch.stack([spin.random(count, c.seed + salt, S["R"], i) for i in range(n)])
+    def trunc_tuple(count, seed):
+        r_sh = torch.stack([spin.random(count, seed, S["R"], i) for i in range(n)])
         r = spin.open(r_sh)
         r_top = (r >> f) & ((1 << (63 - f)) - 1)
         r_msb = (r >> 63) & 1
-        return r_sh, spin.share(r_top, n, c.seed + salt, S["RT"]), spin.share(r_msb, n, c.seed + salt, S["RM"])
-    r1 = trunc_tuple(szC, 0x100)
-    r2 = trunc_tuple(szC, 0x200)
-    # elementwise triple and the second factor of the elementwise product
-    ea = torch.stack([spin.random(szC, c.seed, 11, i) for i in range(n)])
-    eb = torch.stack([spin.random(szC, c.seed, 12, i) for i in range(n)])
-    ec = spin.share(spin.open(ea) * spin.open(eb), n, c.seed, 13)
-    w = spin.share(spin.encode(torch.from_numpy(workloads.vec_plaintexts(args.config, szC)[0]).cuda(), f), n, c.seed,
-                   S["W"])
+        return r_sh, spin.share(r_top, n, seed, S["RT"]), spin.share(r_msb, n, seed, S["RM"])
 
-    Xs = torch.empty((n, batch, M, K), dtype=torch.int64, device="cuda")
-    Ys = torch.empty((n, batch, K, N), dtype=torch.int64, device="cuda")
-    Z = torch.empty((n, batch, M, N), dtype=torch.int64, device="cuda")
-    T = torch.empty((n, szC), dtype=torch.int64, device="cuda")
-    V = torch.empty((n, szC), dtype=torch.int64, device="cuda")
+    def matmul_triple(batch, M, N, K, seed):
+        """A_i, B_i from the generator, C = (sum A_i).(sum B_i) through the library's own ring GEMM (one party, zero
+        triple), then shared: exactly what the oracle's dealer computes.  The GEMM runs on the VALU path so that every
+        limb-GEMM launch a profiler sees belongs to the workload."""
+        A = party_random(batch * M * K, S["A"], (batch, M, K), seed)
+        B = party_random(batch * K * N, S["B"], (batch, K, N), seed)
+        ws1 = torch.empty(spin.beaver_matmul_workspace_bytes(1, batch, M, N, K, spin.VALU), dtype=torch.uint8,
+                          device="cuda")
+        a_open, b_open = spin.open(A)[None], spin.open(B)[None]
+        zC = torch.zeros((1, batch, M, N), dtype=torch.int64, device="cuda")
+        c_plain = spin.beaver_matmul(a_open, b_open, torch.zeros_like(a_open), torch.zeros_like(b_open), zC,
+                                     path=spin.VALU, workspace=ws1)
+        return A, B, spin.share(c_plain[0], n, seed, S["C"])
+
+    def mul_triple(count, seed):
+        ea = torch.stack([spin.random(count, seed, 11, i) for i in range(n)])
+        eb = torch.stack([spin.random(count, seed, 12, i) for i in range(n)])
+        return ea, eb, spin.share(spin.open(ea) * spin.open(eb), n, seed, 13)
+
+    # ---- untimed set-up: plaintexts, triples and truncation tuples, all resident in HBM ----------------
+    steps_list = []                # callables of one step, in order
+    ring_macs = 0.0
+    legs = []
+    gemm_z = []                    # Z of every GEMM leg
+    ws_bytes = 0
+    gemm_plans = []
+    for gi, g in enumerate(c.gemms):
+        Xr, Yr = workloads.gemm_plaintexts(cfg, gi)
+        batch, M, K = Xr.shape
+        N = Yr.shape[2]
+        transposed = g.name == "qkT"               # the key matrix is stored [N][K]: Q.K^T through spin_beaver_matmul_nt
+        gemm_plans.append((gi, g, Xr, Yr, batch, M, N, K, transposed))
+        ws_bytes = max(ws_bytes, spin.beaver_matmul_workspace_bytes(n, batch, M, N, K, path))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    prev_out = None                # truncated shares produced by the previous leg (config 4: the scores feed P.V)
+    for gi, g, Xr, Yr, batch, M, N, K, transposed in gemm_plans:
+        seed = c.seed + 0x10 * gi
+        szA, szB, szC = batch * M * K, batch * K * N, batch * M * N
+        A, B, C = matmul_triple(batch, M, N, K, seed)
+        y_plain = spin.encode(torch.from_numpy(Yr).cuda(), f)
+        if transposed:
+            y_plain = y_plain.transpose(1, 2).contiguous()
+            B = B.transpose(2, 3).contiguous()
+        Ys = torch.empty((n,) + tuple(y_plain.shape), dtype=torch.int64, device="cuda")
+        Z = torch.empty((n, batch, M, N), dtype=torch.int64, device="cuda")
+        T = torch.empty((n, szC), dtype=torch.int64, device="cuda")
+        tup = trunc_tuple(szC, seed + 0x100)
+        chained = cfg == 4 and gi == 1 and prev_out is not None
+        if chained:
+            Xs = prev_out.view(n, batch, M, K)     # P = the multiplied, truncated scores of the previous legs
+            x_plain = None
+        else:
+            x_plain = spin.encode(torch.from_numpy(Xr).cuda(), f)
+            Xs = torch.empty((n, batch, M, K), dtype=torch.int64, device="cuda")
+
+        def leg(x_plain=x_plain, y_plain=y_plain, Xs=Xs, Ys=Ys, A=A, B=B, C=C, Z=Z, T=T, tup=tup, seed=seed,
+                transposed=transposed):
+            if x_plain is not None:
+                spin.share(x_plain, n, seed, S["X"], out=Xs)
+            spin.share(y_plain, n, seed, S["Y"], out=Ys)
+            spin.beaver_matmul(Xs, Ys, A, B, C, path=path, out=Z, workspace=ws, y_transposed=transposed)
+            spin.trunc(Z.view(n, -1), tup[0], tup[1], tup[2], f, out=T)
+        steps_list.append(leg)
+        gemm_z.append(Z)
+        ring_macs += 2.0 * n * batch * M * N * K
+        count_bytes("share", (1 + n) * 8.0 * (szB + (0 if chained else szA)))
+        count_bytes("trunc", 5 * n * 8.0 * szC)
+        fused_left = path == spin.LIMB_MFMA and N <= 64 and n <= 3 and K % 2 == 0   # left fragments built in the GEMM
+        count_bytes("pack", 8.0 * (3 * n + 1) * (szB + (0 if fused_left else szA)))
+        legs.append("%sBeaver matmul %s batch %d M=%d N=%d K=%d (%s) + trunc"
+                    % ("" if chained else "share X, ", g.name, batch, M, N, K,
+                       "share Y, spin_beaver_matmul_nt" if transposed else "share Y, spin_beaver_matmul"))
+        prev_out = T
+        # elementwise leg on this GEMM's truncated output (configs without vectors of their own; config 4: the scores)
+        if (c.vec == 0 and gi == 0) or (cfg == 4 and gi == 0):
+            count = szC
+            ea, eb, ec = mul_triple(count, seed)
+            w = spin.share(spin.encode(torch.from_numpy(workloads.vec_plaintexts(cfg, count)[0]).cuda(), f), n, seed, S["W"])
+            V = torch.empty((n, count), dtype=torch.int64, device="cuda")
+            tup2 = trunc_tuple(count, seed + 0x200)
+
+            def mul_leg(T=T, w=w, ea=ea, eb=eb, ec=ec, V=V, tup2=tup2):
+                if args.fuse_mul_trunc:
+                    spin.beaver_mul_trunc(T, w, ea, eb, ec, tup2[0], tup2[1], tup2[2], f, out=V)
+                else:
+                    spin.beaver_mul(T, w, ea, eb, ec, out=V)
+                    spin.trunc(V, tup2[0], tup2[1], tup2[2], f, out=V)
+            steps_list.append(mul_leg)
+            if args.fuse_mul_trunc:
+                count_bytes("beaver_mul_trunc", 9 * n * 8.0 * count)
+            else:
+                count_bytes("beaver_mul", 6 * n * 8.0 * count)
+                count_bytes("trunc", 5 * n * 8.0 * count)
+            legs.append("elementwise Beaver mul of the result with a shared tensor (%d elements) + trunc" % count)
+            prev_out = V
+    if c.vec and cfg != 4:
+        # the configuration's own vectors (config 2: 2^24 elements): share both, multiply, truncate
+        L = c.vec
+        xr, yr = workloads.vec_plaintexts(cfg)
+        xv = spin.encode(torch.from_numpy(xr).cuda(), f)
+        yv = spin.encode(torch.from_numpy(yr).cuda(), f)
+        Xv = torch.empty((n, L), dtype=torch.int64, device="cuda")
+        Yv = torch.empty((n, L), dtype=torch.int64, device="cuda")
+        ea, eb, ec = mul_triple(L, c.seed + 0x40)
+        tupv = trunc_tuple(L, c.seed + 0x300)
+        Vv = torch.empty((n, L), dtype=torch.int64, device="cuda")
+
+        def vec_leg():
+            spin.share(xv, n, c.seed, S["X"] + 20, out=Xv)
+            spin.share(yv, n, c.seed, S["Y"] + 20, out=Yv)
+            if args.fuse_mul_trunc:
+                spin.beaver_mul_trunc(Xv, Yv, ea, eb, ec, tupv[0], tupv[1], tupv[2], f, out=Vv)
+            else:
+                spin.beaver_mul(Xv, Yv, ea, eb, ec, out=Vv)
+                spin.trunc(Vv, tupv[0], tupv[1], tupv[2], f, out=Vv)
+        steps_list.append(vec_leg)
+        count_bytes("share", 2 * (1 + n) * 8.0 * L)
+        if args.fuse_mul_trunc:
+            count_bytes("beaver_mul_trunc", 9 * n * 8.0 * L)
+        else:
+            count_bytes("beaver_mul", 6 * n * 8.0 * L)
+            count_bytes("trunc", 5 * n * 8.0 * L)
+        legs.append("share + elementwise Beaver mul + trunc on %d-element vectors" % L)
 
     def step():
-        spin.share(x, n, c.seed, S["X"], out=Xs)
-        spin.share(y, n, c.seed, S["Y"], out=Ys)
-        spin.beaver_matmul(Xs, Ys, A, B, C, path=path, out=Z, workspace=ws)
-        spin.trunc(Z.view(n, -1), r1[0], r1[1], r1[2], f, out=T)
-        if args.fuse_mul_trunc:
-            spin.beaver_mul_trunc(T, w, ea, eb, ec, r2[0], r2[1], r2[2], f, out=V)
-        else:
-            spin.beaver_mul(T, w, ea, eb, ec, out=V)
-            spin.trunc(V, r2[0], r2[1], r2[2], f, out=V)
+        for leg in steps_list:
+            leg()
 
     # one plain copy of known size (open of a single share: out[k] = shares[0][k]); the HBM byte counters
     # of a profiler run are calibrated against what they read for this launch (1 GiB in, 1 GiB out)
@@ -384,65 +474,102 @@ def main():
         step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    ring_macs = 2.0 * n * batch * M * N * K
     kernels = {k: spin.profile_read(k) for k in spin.KERNELS}
     spin.profile_reset()
     gemm_key = "gemm_limb" if path == spin.LIMB_MFMA else "gemm_valu"
     gemm_ms, gemm_launches = kernels[gemm_key]
+    pack_ms = kernels["pack"][0] if path == spin.LIMB_MFMA else kernels["open"][0]
     launches_per_step = gemm_launches / args.steps
     gemm_avg_ms = gemm_ms / gemm_launches
+    gemm_ms_per_step = gemm_ms / args.steps
     if path == spin.LIMB_MFMA:
-        ops_per_launch = ring_macs * INT8_OPS_PER_RING_MAC / launches_per_step
-        achieved = ops_per_launch / (gemm_avg_ms * 1e-3) / 1e12
+        # all GEMM launches of a step together: algorithmic int8 operations / their summed kernel time
+        achieved = ring_macs * INT8_OPS_PER_RING_MAC / (gemm_ms_per_step * 1e-3) / 1e12
+        with_pack = ring_macs * INT8_OPS_PER_RING_MAC / ((gemm_ms + pack_ms) / args.steps * 1e-3) / 1e12
+        traffic = measured_traffic("limb_gemm_kernel", cfg)
         roofline = {"bound": "mfma", "kernel": "limb_gemm_kernel", "achieved": achieved, "peak": PEAK_INT8_TOPS,
-                    "unit": "TOP/s", "frac": achieved / PEAK_INT8_TOPS,
-                    "traffic": measured_traffic("limb_gemm_kernel", args.config),
+                    "unit": "TOP/s", "frac": achieved / PEAK_INT8_TOPS, "traffic": traffic,
+                    "traffic_source": ("profiles/config%d_step_hbm_traffic.txt: rocprofv3 FETCH_SIZE / WRITE_SIZE of an "
+                                       "earlier run of this command, not measured in this run" % cfg) if traffic else None,
                     "avg_launch_ms": gemm_avg_ms, "launches_per_step": launches_per_step,
-                    "ring_mac_per_s": ring_macs / launches_per_step / (gemm_avg_ms * 1e-3)}
+                    "ring_mac_per_s": ring_macs / (gemm_ms_per_step * 1e-3),
+                    "frac_with_pack": with_pack / PEAK_INT8_TOPS,
+                    "note": "frac = int8 operations of all limb-GEMM launches of a step / their kernel time; frac_with_pack "
+                            "also counts the pack kernels that open E, F and split the operands into digits"}
     else:
         # 64-bit multiply-add on the vector ALU: 256 CUs x 4 SIMDs x 16 lanes per clock at 2.4 GHz; the compiled
         # inner loop spends four VALU instructions per ring MAC (v_mad_u64_u32, 2 x v_mul_lo_u32, v_add3_u32),
         # each taken at full rate
         peak = 256 * 4 * 16 * 2.4e9 / 4 / 1e12
-        achieved = ring_macs / launches_per_step / (gemm_avg_ms * 1e-3) / 1e12
+        achieved = ring_macs / (gemm_ms_per_step * 1e-3) / 1e12
         roofline = {"bound": "alu", "kernel": "valu_gemm_kernel", "achieved": achieved, "peak": peak,
-                    "unit": "T ring MAC/s", "frac": achieved / peak, "traffic": None, "avg_launch_ms": gemm_avg_ms,
-                    "launches_per_step": launches_per_step}
-    # HBM-bound side kernels, for the record: algorithmic bytes / event time
-    el = 8.0 * szC
+                    "unit": "T ring MAC/s", "frac": achieved / peak, "traffic": None, "traffic_source": None,
+                    "avg_launch_ms": gemm_avg_ms, "launches_per_step": launches_per_step}
+    # HBM-bound side kernels: algorithmic bytes of all their launches in a step / their summed event time
     streams = {}
-    per_call_bytes = {"share": (1 + n) * 8.0 * (szA + szB) / 2, "trunc": 5 * n * el, "beaver_mul": 6 * n * el,
-                      "pack": 8.0 * ((2 * n + n + 1) * szA + (2 * n + n + 1) * szB),
-                      "beaver_mul_trunc": 9 * n * el}
-    for k, b in per_call_bytes.items():
+    for k, b in alg_bytes.items():
         ms, cnt = kernels[k]
         if cnt:
-            streams[k] = {"GB/s": b / (ms / cnt * 1e-3) / 1e9, "frac_hbm": b / (ms / cnt * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                          "avg_ms": ms / cnt}
+            rate = b * args.steps / (ms * 1e-3) / 1e9
+            streams[k] = {"GB/s": rate, "frac_hbm": rate / PEAK_HBM_GBS, "avg_ms": ms / cnt,
+                          "launches_per_step": cnt / args.steps, "algorithmic_bytes_per_step": b}
+    g0 = c.gemms[0]
     out = {
         "metric": "Z_2^64 ring MACs/s for Beaver matmul (1 GPU)", "value": ring_macs / (ms_per_step * 1e-3),
         "unit": "ring MAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u64 (int8 digits, int32 accumulate)" if path == spin.LIMB_MFMA else "u64",
         "data": "synthetic",
-        "config": {"workload": "config %d: %d parties, batch %d, M=%d N=%d K=%d, f=%d, %s; step = share X,Y + Beaver "
-                               "matmul (open+update) + trunc + elementwise Beaver mul + trunc" %
-                               (args.config, n, batch, M, N, K, f, c.dist),
+        "config": {"workload": "config %d: %d parties, f=%d, %s; step = %s" % (cfg, n, f, c.dist, "; then ".join(legs)),
                    "gemm_path": args.path, "parties": n, "launch": "hip graph replay" if args.graph else "eager",
-                   "mul_trunc": "one pass" if args.fuse_mul_trunc else "two calls"},
+                   "mul_trunc": "one pass" if args.fuse_mul_trunc else "two calls",
+                   "ring_macs_per_step": ring_macs},
         "roofline": roofline, "stream_kernels": streams,
         "step_ms_median": step_ms[len(step_ms) // 2] if step_ms else None, "step_ms_min": step_ms[0] if step_ms else None,
         "limb_roofline_ring_mac_per_s": PEAK_INT8_TOPS * 1e12 / INT8_OPS_PER_RING_MAC,
         # the protocol's view: one secure product of the plaintext shapes per step, whatever n
-        "secure_matmul_mac_per_s": batch * M * N * K / (ms_per_step * 1e-3),
+        "secure_matmul_mac_per_s": ring_macs / (2 * n) / (ms_per_step * 1e-3),
     }
-    if path == spin.LIMB_MFMA:
+    if path == spin.LIMB_MFMA and args.mfma_ceiling:
         out["mfma_ceiling"] = mfma_ceiling(roofline["achieved"])
     if not args.no_cpu_baseline:
-        del Xs, Ys, Z, T, V, ws
+        Z0 = gemm_z[0]
+
+        def gpu_rows(rows):
+            idx = torch.from_numpy(np.asarray(rows, dtype=np.int64)).cuda()
+            return Z0.index_select(2, idx).cpu().numpy().view(np.uint64)
+        steps_list.clear()
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(args.config, args.cpu_seconds)
-    print(json.dumps(out))
+        out["cpu_baseline"], out["parity_rows_checked"] = cpu_baseline(cfg, args.cpu_seconds, gpu_rows)
+        out["parity"] = ("rows of the first GEMM's Z, as left by the timed steps, equal the oracle's word for word "
+                         "(rows x batch entries, every party)")
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (all parties' shares live on one MI355X); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2402_02320_amd import spin
+    if not os.path.exists(spin.LIB_PATH):
+        from paper_2402_02320_amd import build
+        build.build()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    if args.workload == "poly":
+        args.config = 5 if args.config == "all" else int(args.config)
+        return bench_poly(args)
+    if args.workload in ("matmul128", "matmul32"):
+        return bench_matmul_other_ring(args, 128 if args.workload == "matmul128" else 32)
+    configs = [1, 2, 3, 4, 5] if args.config == "all" else [int(args.config)]
+    for cfg in configs:
+        print(json.dumps(run_config(args, cfg)), flush=True)
+        torch.cuda.empty_cache()
 
 
 if __name__ == "__main__":
