@@ -318,8 +318,10 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
 // Z_2^64 products whose output is a single column tile (N <= 64): every left fragment would be used by
 // exactly one output tile, so writing the left operands out as fragments and reading them back (the pack
 // pre-pass) costs more HBM traffic than the product itself.  Here the left fragments never exist in
-// memory.  One workgroup owns a block of 32 rows for ALL parties (NP <= 3) and walks the inner dimension
-// once; the raw 32 x 32 tiles of every X_j and A_j go memory -> LDS exactly once (direct-to-LDS loads,
+// memory.  (Products of a few column tiles and a short inner dimension -- the attention shapes -- take the
+// same kernel once per column tile when that is cheaper than the pre-pass: the raw tiles are then read once
+// per column tile, from L2.)  One workgroup owns a block of 32 rows and one column tile of 64 for ALL
+// parties (NP <= 3) and walks the inner dimension once; the raw 32 x 32 tiles of every X_j and A_j go memory -> LDS exactly once (direct-to-LDS loads,
 // no register is held while they fly).
 //   producer wave (the last one, on a SIMD of its own)  issues those loads one k-tile ahead, opens
 //       E = sum_j (X_j - A_j) from the raw tiles, converts E to digits and lays it out as MFMA fragments
@@ -338,10 +340,10 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
 // slot (g+1) % 2, writes E(g+1) to stage (g+1) % 2 and refills raw slot g % 2 with k-tile g + 2.
 struct RowGemmArgs {
     const u64 *X, *A;        // [n][batch][M][K]
-    const char *packB;       // right fragment store [n+1][batch][2][KT][8][1024]: slot 0 = F, 1 + i = B_i'
+    const char *packB;       // right fragment store [n+1][batch][2 tilesN][KT][8][1024]: slot 0 = F, 1 + i = B_i'
     const u64 *C;            // [n][batch][M][N]
     u64 *Z;
-    int batch, M, N, K, KT;
+    int batch, M, N, K, KT, tilesN;
 };
 
 // Raw tile in LDS: 64 groups of 128 bytes, group 2 r + h = the 16 consecutive k (8 pieces of 16 bytes) of
@@ -394,7 +396,7 @@ __global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmAr
     const int lane = threadIdx.x % 64;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
     const int rblocks = (g.M + 31) / 32;
-    const int b = blockIdx.x / rblocks, rb = blockIdx.x % rblocks;
+    const int rb = blockIdx.x % rblocks, tn = blockIdx.x / rblocks % g.tilesN, b = blockIdx.x / rblocks / g.tilesN;
     const int KT = g.KT;
     lds_char *lds3 = (lds_char *)lds;
     lds_char *e_ring = lds3 + 2 * kRawSlot;
@@ -476,8 +478,8 @@ __global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmAr
     // the lane's 16 bytes as the only vector offset, the k-tile and column block in a scalar offset, the
     // digit as the immediate -- so the 32 loads of a k-tile need no per-lane address arithmetic.
     const u32 cb_stride = (u32)KT * (8 * kFrag);         // from column block 0 to column block 1 (< 2^22)
-    const char *f_base = g.packB + (size_t)b * 2 * cb_stride;                            // F
-    const char *b_base = g.packB + ((size_t)(1 + party) * g.batch + b) * 2 * cb_stride;  // B_p'
+    const char *f_base = g.packB + ((size_t)b * g.tilesN + tn) * 2 * cb_stride;                              // F
+    const char *b_base = g.packB + (((size_t)(1 + party) * g.batch + b) * g.tilesN + tn) * 2 * cb_stride;    // B_p'
     const __amdgpu_buffer_rsrc_t f_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)f_base, 0, 2 * cb_stride, 0x00020000);
     const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)b_base, 0, 2 * cb_stride, 0x00020000);
     lds_char *a_raw = lds3 + party * (2 * kRawTile) + kRawTile;      // raw A_p in raw slot 0
@@ -599,10 +601,10 @@ __global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmAr
     const size_t zmat = (size_t)g.M * g.N;
     const u64 *Cm = g.C + ((size_t)party * g.batch + b) * zmat;
     u64 *Zm = g.Z + ((size_t)party * g.batch + b) * zmat;
-    const bool interior = (rb + 1) * 32 <= g.M && g.N == 64;
+    const bool interior = (rb + 1) * 32 <= g.M && (tn + 1) * 64 <= g.N;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        const int col = j * 32 + lane % 32;
+        const int col = tn * 64 + j * 32 + lane % 32;
         const int row0 = rb * 32 + 4 * (lane / 32);
         auto row_of = [&](int r) { return row0 + 8 * (r / 4) + r % 4; };
         u64 v[16];
@@ -671,20 +673,21 @@ inline int choose_splits(long tiles, int steps)
     return best;
 }
 
-// Whether the row-streaming kernel takes a product: 64-bit ring, one column tile, at most three parties
-// (one consumer wave each), even K (16-byte row alignment), an inner dimension one launch may accumulate,
-// and a lower estimated cost than the tile kernel plus its pre-pass over the left operands.  Costs are in
-// k-steps of one CU (about a microsecond), the unit of choose_splits: the row kernel walks 2 KT steps per
-// block of 32 rows; the other path adds the left pack, an HBM stream of (3n + 1) operand-sized matrices at
-// about 5 MB per step-time, and one more launch.
+// Whether the row-streaming kernel takes a product: 64-bit ring, at most three parties (one consumer wave
+// each), even K (16-byte row alignment), an inner dimension one launch may accumulate, and a lower
+// estimated cost than the tile kernel plus its pre-pass over the left operands.  Costs are in k-steps of
+// one CU (about a microsecond), the unit of choose_splits: the row kernel walks 2 KT steps per block of 32
+// rows and column tile; the other path adds the left pack, an HBM stream of (3n + 1) operand-sized matrices
+// at about 5 MB per step-time, and one more launch.
 template <class T> inline bool rows_kernel_applies(const MatmulArgsT<T> &a, const Plan &p)
 {
     if (!std::is_same<T, u64>::value) return false;
-    if (p.tilesN != 1 || a.n > 3 || a.K % 2 != 0 || p.KT > Ring<u64>::max_chunk_tiles) return false;
+    if (a.n > 3 || a.K % 2 != 0 || p.KT > Ring<u64>::max_chunk_tiles) return false;
     const int cus = compute_units();
-    const long rblocks = (long)a.batch * ceil_div(a.M, 32);
+    const long rblocks = (long)a.batch * ceil_div(a.M, 32) * p.tilesN;
+    if (rblocks > 0x7fffffffL) return false;
     const double cost_rows = (double)((rblocks + cus - 1) / cus) * (2 * p.KT + 8);
-    const long tiles = (long)p.tilesM * a.n * a.batch;
+    const long tiles = (long)p.tilesM * p.tilesN * a.n * a.batch;
     const int sp = choose_splits(tiles, 2 * p.KT);
     const double pack_bytes = 8.0 * (3 * a.n + 1) * a.batch * (double)a.M * a.K;
     const double cost_tiles = (double)((tiles * sp + cus - 1) / cus) * (2 * ceil_div(p.KT, sp) + 8) + pack_bytes / 5.0e6 + 5;
@@ -700,8 +703,8 @@ inline spin_status launch_rows(const MatmulArgs &a, const Plan &p, char *packB, 
         spin_status st = check_launch(where_pack);
         if (st != SPIN_OK) return st;
     }
-    RowGemmArgs g{a.X, a.A, packB, a.C, a.Z, a.batch, a.M, a.N, a.K, p.KT};
-    const unsigned grid = (unsigned)((long)a.batch * ceil_div(a.M, 32));
+    RowGemmArgs g{a.X, a.A, packB, a.C, a.Z, a.batch, a.M, a.N, a.K, p.KT, p.tilesN};
+    const unsigned grid = (unsigned)((long)a.batch * ceil_div(a.M, 32) * p.tilesN);
     spin_status st = SPIN_OK;
     for_party_count(a.n, [&](auto np) {
         constexpr int NP = decltype(np)::value <= 3 ? decltype(np)::value : 3;   // n <= 3 is checked by the caller
