@@ -49,6 +49,8 @@ typedef enum {
     SPIN_EHIP = 4        /* a launch failed; spin_last_hip_error() holds the runtime's message        */
 } spin_status;
 
+/* The `path` argument of the matmul calls.  It is passed as an int so that a value outside the
+ * enumeration is refused with SPIN_EINVAL instead of being undefined behaviour on the library's side. */
 typedef enum {
     SPIN_GEMM_LIMB_MFMA = 0, /* exact 8-bit-limb decomposition on int8 MFMA, int32 accumulation */
     SPIN_GEMM_VALU = 1       /* 64-bit multiply-add on the vector ALU (baseline)                */
@@ -94,7 +96,7 @@ spin_status spin_open(const uint64_t *shares, const uint64_t *mask, size_t count
 spin_status spin_beaver_matmul(int n, int batch, int M, int N, int K,
                                const uint64_t *X, const uint64_t *Y,
                                const uint64_t *A, const uint64_t *B, const uint64_t *C,
-                               uint64_t *Z, spin_gemm_path path,
+                               uint64_t *Z, int path,
                                void *workspace, size_t workspace_bytes, spin_stream stream);
 
 /* The same with the right operands stored transposed, the layout of K in the attention product
@@ -104,7 +106,7 @@ spin_status spin_beaver_matmul(int n, int batch, int M, int N, int K,
 spin_status spin_beaver_matmul_nt(int n, int batch, int M, int N, int K,
                                   const uint64_t *X, const uint64_t *Yt,
                                   const uint64_t *A, const uint64_t *Bt, const uint64_t *C,
-                                  uint64_t *Z, spin_gemm_path path,
+                                  uint64_t *Z, int path,
                                   void *workspace, size_t workspace_bytes, spin_stream stream);
 
 /* An array of Beaver matmuls of different shapes in one call (Section 7.4's PMatMul takes arrays of
@@ -122,13 +124,13 @@ typedef struct {
     uint64_t *Z;
     int y_transposed;
 } spin_matmul_group;
-spin_status spin_beaver_matmul_grouped(int n, int groups, const spin_matmul_group *desc, spin_gemm_path path,
+spin_status spin_beaver_matmul_grouped(int n, int groups, const spin_matmul_group *desc, int path,
                                        void *workspace, size_t workspace_bytes, spin_stream stream);
 size_t spin_beaver_matmul_grouped_workspace_bytes(int n, int groups, const spin_matmul_group *desc,
-                                                  spin_gemm_path path);
+                                                  int path);
 
 /* Bytes of workspace spin_beaver_matmul needs; 0 if the arguments are invalid. */
-size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path);
+size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, int path);
 
 /* spin_beaver_matmul for callers that cannot allocate device memory, and so cannot bring a workspace:
  * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
@@ -145,7 +147,7 @@ size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K,
 spin_status spin_beaver_matmul_static(int n, int batch, int M, int N, int K,
                                       const uint64_t *X, const uint64_t *Y,
                                       const uint64_t *A, const uint64_t *B, const uint64_t *C,
-                                      uint64_t *Z, spin_gemm_path path, spin_stream stream);
+                                      uint64_t *Z, int path, spin_stream stream);
 
 /* Online phase of elementwise multiplication with scalar triples (Section 4.3;
  * the "batch multiplication" of Section 7.3):
@@ -244,9 +246,9 @@ spin_status spin128_open(const uint64_t *shares, const uint64_t *mask, size_t co
 spin_status spin128_beaver_matmul(int n, int batch, int M, int N, int K,
                                   const uint64_t *X, const uint64_t *Y,
                                   const uint64_t *A, const uint64_t *B, const uint64_t *C,
-                                  uint64_t *Z, spin_gemm_path path,
+                                  uint64_t *Z, int path,
                                   void *workspace, size_t workspace_bytes, spin_stream stream);
-size_t spin128_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path);
+size_t spin128_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, int path);
 spin_status spin128_beaver_mul(int n, size_t count,
                                const uint64_t *x, const uint64_t *y,
                                const uint64_t *a, const uint64_t *b, const uint64_t *c,
@@ -274,9 +276,9 @@ spin_status spin32_open(const uint32_t *shares, const uint32_t *mask, size_t cou
 spin_status spin32_beaver_matmul(int n, int batch, int M, int N, int K,
                                  const uint32_t *X, const uint32_t *Y,
                                  const uint32_t *A, const uint32_t *B, const uint32_t *C,
-                                 uint32_t *Z, spin_gemm_path path,
+                                 uint32_t *Z, int path,
                                  void *workspace, size_t workspace_bytes, spin_stream stream);
-size_t spin32_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path);
+size_t spin32_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, int path);
 spin_status spin32_beaver_mul(int n, size_t count,
                               const uint32_t *x, const uint32_t *y,
                               const uint32_t *a, const uint32_t *b, const uint32_t *c,
@@ -287,7 +289,7 @@ spin_status spin32_trunc(int n, size_t count, int f, const uint32_t *x,
 spin_status spin_cast_64_to_32(const uint64_t *in, size_t count, uint32_t *out, spin_stream stream);
 
 /* Static description of a status code. */
-const char *spin_status_string(spin_status status);
+const char *spin_status_string(int status);
 
 /* Message of the most recent HIP failure seen by this thread ("" if none). */
 const char *spin_last_hip_error(void);

@@ -42,7 +42,7 @@ typedef enum {
     SPIN_KERNEL_COUNT = 13
 } spin_kernel;
 void spin_profile_enable(int on);
-spin_status spin_profile_read(spin_kernel kernel, double *total_ms, unsigned *launches);
+spin_status spin_profile_read(int kernel, double *total_ms, unsigned *launches);
 void spin_profile_reset(void);
 
 /* Measurement aid: the int8 matrix-core rate the chip sustains on given operand bytes.  Every wave

@@ -146,7 +146,7 @@ static spin_status check_matmul_dims(int n, int batch, int M, int N, int K)
     return SPIN_OK;
 }
 
-size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path)
+size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, int path)
 {
     if (check_matmul_dims(n, batch, M, N, K) != SPIN_OK) return 0;
     if (path == SPIN_GEMM_LIMB_MFMA) return limb_workspace_bytes(n, batch, M, N, K);
@@ -157,7 +157,7 @@ size_t spin_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K,
 // Everything spin_beaver_matmul checks except the workspace; touches no HIP call.
 static spin_status check_matmul64(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Y,
                                   const uint64_t *A, const uint64_t *B, const uint64_t *C, uint64_t *Z,
-                                  spin_gemm_path path)
+                                  int path)
 {
     if (bad_ptr(X) || bad_ptr(Y) || bad_ptr(A) || bad_ptr(B) || bad_ptr(C) || bad_ptr(Z)) return SPIN_EINVAL;
     if (path != SPIN_GEMM_LIMB_MFMA && path != SPIN_GEMM_VALU) return SPIN_EINVAL;
@@ -166,7 +166,7 @@ static spin_status check_matmul64(int n, int batch, int M, int N, int K, const u
 
 static spin_status beaver_matmul64(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Y,
                                    const uint64_t *A, const uint64_t *B, const uint64_t *C, uint64_t *Z,
-                                   spin_gemm_path path, void *workspace, size_t workspace_bytes, spin_stream stream,
+                                   int path, void *workspace, size_t workspace_bytes, spin_stream stream,
                                    bool y_transposed)
 {
     spin_status st = check_matmul64(n, batch, M, N, K, X, Y, A, B, C, Z, path);
@@ -181,19 +181,19 @@ static spin_status beaver_matmul64(int n, int batch, int M, int N, int K, const 
 
 spin_status spin_beaver_matmul(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Y,
                                const uint64_t *A, const uint64_t *B, const uint64_t *C, uint64_t *Z,
-                               spin_gemm_path path, void *workspace, size_t workspace_bytes, spin_stream stream)
+                               int path, void *workspace, size_t workspace_bytes, spin_stream stream)
 {
     return beaver_matmul64(n, batch, M, N, K, X, Y, A, B, C, Z, path, workspace, workspace_bytes, stream, false);
 }
 
 spin_status spin_beaver_matmul_nt(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Yt,
                                   const uint64_t *A, const uint64_t *Bt, const uint64_t *C, uint64_t *Z,
-                                  spin_gemm_path path, void *workspace, size_t workspace_bytes, spin_stream stream)
+                                  int path, void *workspace, size_t workspace_bytes, spin_stream stream)
 {
     return beaver_matmul64(n, batch, M, N, K, X, Yt, A, Bt, C, Z, path, workspace, workspace_bytes, stream, true);
 }
 
-size_t spin_beaver_matmul_grouped_workspace_bytes(int n, int groups, const spin_matmul_group *desc, spin_gemm_path path)
+size_t spin_beaver_matmul_grouped_workspace_bytes(int n, int groups, const spin_matmul_group *desc, int path)
 {
     if (desc == nullptr || groups < 1 || groups > SPIN_MAX_GROUPS) return 0;
     size_t need = 0;
@@ -205,7 +205,7 @@ size_t spin_beaver_matmul_grouped_workspace_bytes(int n, int groups, const spin_
     return need;
 }
 
-spin_status spin_beaver_matmul_grouped(int n, int groups, const spin_matmul_group *desc, spin_gemm_path path,
+spin_status spin_beaver_matmul_grouped(int n, int groups, const spin_matmul_group *desc, int path,
                                        void *workspace, size_t workspace_bytes, spin_stream stream)
 {
     if (desc == nullptr || groups < 1 || groups > SPIN_MAX_GROUPS) return SPIN_EINVAL;
@@ -266,7 +266,7 @@ extern "C" {
 
 spin_status spin_beaver_matmul_static(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Y,
                                       const uint64_t *A, const uint64_t *B, const uint64_t *C, uint64_t *Z,
-                                      spin_gemm_path path, spin_stream stream)
+                                      int path, spin_stream stream)
 {
     spin_status st = check_matmul64(n, batch, M, N, K, X, Y, A, B, C, Z, path);
     if (st != SPIN_OK) return st;
@@ -335,7 +335,7 @@ void spin_profile_reset(void)
     g_timed.clear();
 }
 
-spin_status spin_profile_read(spin_kernel kernel, double *total_ms, unsigned *launches)
+spin_status spin_profile_read(int kernel, double *total_ms, unsigned *launches)
 {
     if (!total_ms || !launches || kernel < 0 || kernel >= SPIN_KERNEL_COUNT) return SPIN_EINVAL;
     double sum = 0.0;
@@ -425,7 +425,7 @@ spin_status spin128_open(const uint64_t *shares, const uint64_t *mask, size_t co
     return launch_open<u128>(r128(shares), r128(mask), count, n, r128(out), (hipStream_t)stream);
 }
 
-size_t spin128_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path)
+size_t spin128_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, int path)
 {
     if (check_matmul_dims(n, batch, M, N, K) != SPIN_OK) return 0;
     if (path == SPIN_GEMM_LIMB_MFMA) return limb128_workspace_bytes(n, batch, M, N, K);
@@ -435,7 +435,7 @@ size_t spin128_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int
 
 spin_status spin128_beaver_matmul(int n, int batch, int M, int N, int K, const uint64_t *X, const uint64_t *Y,
                                   const uint64_t *A, const uint64_t *B, const uint64_t *C, uint64_t *Z,
-                                  spin_gemm_path path, void *workspace, size_t workspace_bytes, spin_stream stream)
+                                  int path, void *workspace, size_t workspace_bytes, spin_stream stream)
 {
     if (bad_ptr(X) || bad_ptr(Y) || bad_ptr(A) || bad_ptr(B) || bad_ptr(C) || bad_ptr(Z)) return SPIN_EINVAL;
     if (path != SPIN_GEMM_LIMB_MFMA && path != SPIN_GEMM_VALU) return SPIN_EINVAL;
@@ -488,7 +488,7 @@ spin_status spin32_open(const uint32_t *shares, const uint32_t *mask, size_t cou
     return launch_open<u32>(shares, mask, count, n, out, (hipStream_t)stream);
 }
 
-size_t spin32_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, spin_gemm_path path)
+size_t spin32_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int K, int path)
 {
     if (check_matmul_dims(n, batch, M, N, K) != SPIN_OK) return 0;
     if (path == SPIN_GEMM_LIMB_MFMA) return limb32_workspace_bytes(n, batch, M, N, K);
@@ -498,7 +498,7 @@ size_t spin32_beaver_matmul_workspace_bytes(int n, int batch, int M, int N, int 
 
 spin_status spin32_beaver_matmul(int n, int batch, int M, int N, int K, const uint32_t *X, const uint32_t *Y,
                                  const uint32_t *A, const uint32_t *B, const uint32_t *C, uint32_t *Z,
-                                 spin_gemm_path path, void *workspace, size_t workspace_bytes, spin_stream stream)
+                                 int path, void *workspace, size_t workspace_bytes, spin_stream stream)
 {
     if (bad_ptr(X) || bad_ptr(Y) || bad_ptr(A) || bad_ptr(B) || bad_ptr(C) || bad_ptr(Z)) return SPIN_EINVAL;
     if (path != SPIN_GEMM_LIMB_MFMA && path != SPIN_GEMM_VALU) return SPIN_EINVAL;
@@ -545,7 +545,7 @@ spin_status spin_probe_mfma(const uint64_t *operands, int blocks, int iters, uin
     return launch_mfma_probe(operands, blocks, iters, sink, (hipStream_t)stream);
 }
 
-const char *spin_status_string(spin_status status)
+const char *spin_status_string(int status)
 {
     switch (status) {
     case SPIN_OK: return "ok";
