@@ -42,10 +42,11 @@ def parse():
     ap.add_argument("--config", default="5", choices=["1", "2", "3", "4", "5", "all"],
                     help="benchmark configuration (default 5, the headline); all: one JSON line per configuration")
     ap.add_argument("--path", default="limb", choices=["limb", "valu"])
-    ap.add_argument("--workload", default="matmul", choices=["matmul", "poly", "matmul128", "matmul32"],
+    ap.add_argument("--workload", default="matmul", choices=["matmul", "poly", "matmul128", "matmul32", "grouped"],
                     help="matmul: the Beaver-matmul hot path (the benchmark); poly: completed-square polynomial "
                          "evaluation (Section 7.2 Eq. (4)) on the configuration's vector length; matmul128 / matmul32: the "
-                         "Beaver matmul over the other two ring widths")
+                         "Beaver matmul over the other two ring widths; grouped: the attention products of three "
+                         "LeViT-like stages submitted as one spin_beaver_matmul_grouped call against one call per product")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time its replays (for the launch-bound small "
                          "configurations; the per-kernel figures then come from a separate eager pass)")
@@ -272,6 +273,59 @@ def bench_matmul_other_ring(args, bits):
                       "data": "synthetic",
                       "config": {"workload": "%d parties, M=N=K=%d over Z_2^%d" % (n, M, bits), "gemm_path": args.path},
                       "roofline": roof, "gemm_avg_ms": gemm_ms, "pack_avg_ms": pk / pc if pc else None}))
+
+
+def bench_grouped(args):
+    """Side workload (Section 7.4, PMatMul): the Q.K^T and P.V products of three attention stages of different
+    shapes (196, 49 and 16 tokens), 3 parties, as ONE grouped call (shared launches) and as one call per product,
+    both eager on the same stream."""
+    import torch
+    from paper_2402_02320_amd import spin
+    n = 3
+    shapes = [(4, 196, 196, 64, True), (4, 196, 64, 196, False), (8, 49, 49, 32, True), (8, 49, 32, 49, False),
+              (12, 16, 16, 32, True), (12, 16, 32, 16, False)]
+
+    def rnd(shape):
+        return torch.empty(shape, dtype=torch.int64, device="cuda").random_(-2 ** 62, 2 ** 62)
+    groups, macs = [], 0.0
+    for batch, M, N, K, yt in shapes:
+        yshape = (n, batch, N, K) if yt else (n, batch, K, N)
+        groups.append({"X": rnd((n, batch, M, K)), "Y": rnd(yshape), "A": rnd((n, batch, M, K)), "B": rnd(yshape),
+                       "C": rnd((n, batch, M, N)), "out": torch.empty((n, batch, M, N), dtype=torch.int64, device="cuda"),
+                       "y_transposed": yt})
+        macs += 2.0 * n * batch * M * N * K
+    ws = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+
+    def grouped():
+        spin.beaver_matmul_grouped(groups, workspace=ws)
+
+    def one_by_one():
+        for g in groups:
+            spin.beaver_matmul(g["X"], g["Y"], g["A"], g["B"], g["C"], out=g["out"], workspace=ws,
+                               y_transposed=g["y_transposed"])
+    res = {}
+    for name, fn in (("grouped", grouped), ("one_call_per_product", one_by_one)):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        res[name] = (time.perf_counter() - t0) * 1e3 / args.steps
+    ref = [g["out"].clone() for g in groups]
+    grouped()
+    torch.cuda.synchronize()
+    same = all(torch.equal(a, g["out"]) for a, g in zip(ref, groups))
+    print(json.dumps({"metric": "Z_2^64 ring MACs/s, grouped Beaver matmuls of three attention stages (side workload)",
+                      "value": macs / (res["grouped"] * 1e-3), "unit": "ring MAC/s", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "ms_per_step": res["grouped"], "higher_is_better": True, "vs_baseline": None,
+                      "dtype": "u64 (int8 digits, int32 accumulate)", "data": "synthetic",
+                      "config": {"workload": "3 parties, 6 products (batch, M, N, K, right operand transposed): %s" % shapes,
+                                 "launch": "eager"},
+                      "ms_one_call_per_product": res["one_call_per_product"],
+                      "speedup_over_one_call_per_product": res["one_call_per_product"] / res["grouped"],
+                      "same_words_as_one_call_per_product": same}))
 
 
 def run_config(args, cfg):
@@ -566,6 +620,8 @@ def main():
         return bench_poly(args)
     if args.workload in ("matmul128", "matmul32"):
         return bench_matmul_other_ring(args, 128 if args.workload == "matmul128" else 32)
+    if args.workload == "grouped":
+        return bench_grouped(args)
     configs = [1, 2, 3, 4, 5] if args.config == "all" else [int(args.config)]
     for cfg in configs:
         print(json.dumps(run_config(args, cfg)), flush=True)

@@ -110,13 +110,16 @@ spin_status spin_beaver_matmul_nt(int n, int batch, int M, int N, int K,
                                   void *workspace, size_t workspace_bytes, spin_stream stream);
 
 /* An array of Beaver matmuls of different shapes in one call (Section 7.4's PMatMul takes arrays of
- * matrices; products of one shape go into the batch dimension of a group, different shapes into
- * different groups).  desc: HOST array of `groups` descriptors, read before the call returns; every
- * group is what spin_beaver_matmul (y_transposed == 0) or spin_beaver_matmul_nt (!= 0) would be given,
- * with the common party count n.  The groups are enqueued one after another on `stream` and share the
- * workspace, which must hold the largest of them:
- * spin_beaver_matmul_grouped_workspace_bytes(n, groups, desc, path), 0 if a descriptor is invalid.
- * All descriptors are validated before the first launch.  1 <= groups <= SPIN_MAX_GROUPS.         */
+ * matrices and multiplies them in parallel; products of one shape go into the batch dimension of a group,
+ * different shapes into different groups).  desc: HOST array of `groups` descriptors, read before the call
+ * returns; every group is what spin_beaver_matmul (y_transposed == 0) or spin_beaver_matmul_nt (!= 0) would
+ * be given, with the common party count n.  On the limb path the groups share launches -- the operand packs
+ * of all groups first, then their GEMMs, a handful of launches whatever the number of groups -- and every
+ * group has its own part of the workspace, so the workspace must hold the SUM of the groups' needs
+ * (the baseline path enqueues the groups one after another and needs the largest):
+ * spin_beaver_matmul_grouped_workspace_bytes(n, groups, desc, path), 0 if a descriptor is invalid.  All
+ * descriptors are validated before the first launch.  The Z of different groups must not overlap (their
+ * GEMMs run concurrently).  1 <= groups <= SPIN_MAX_GROUPS.                                       */
 #define SPIN_MAX_GROUPS 64
 typedef struct {
     int batch, M, N, K;

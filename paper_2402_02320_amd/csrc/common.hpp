@@ -118,6 +118,9 @@ size_t valu_workspace_bytes(int n, int batch, int M, int N, int K, int elem_byte
 template <class T> spin_status launch_matmul_valu(const MatmulArgsT<T> &a, hipStream_t s);
 size_t limb_workspace_bytes(int n, int batch, int M, int N, int K);
 spin_status launch_matmul_limb(const MatmulArgs &a, hipStream_t s);
+// groups of different shapes in shared launches (a[g].workspace is ignored: every group gets its own part of `workspace`)
+size_t limb_grouped_workspace_bytes(int n, int groups, const MatmulArgs *a);
+spin_status launch_matmul_limb_grouped(int n, int groups, const MatmulArgs *a, void *workspace, hipStream_t s);
 size_t limb32_workspace_bytes(int n, int batch, int M, int N, int K);
 spin_status launch_matmul_limb32(const MatmulArgs32 &a, hipStream_t s);
 spin_status launch_mfma_probe(const u64 *operands, int blocks, int iters, u64 *sink, hipStream_t s);

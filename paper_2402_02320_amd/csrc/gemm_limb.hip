@@ -23,6 +23,9 @@
 //  limb_gemm_kernel  per party: Z_i = C_i + [E | A_i] . [B_i' ; F], fragments
 //                streamed global -> LDS with direct-to-LDS loads, 36 MFMAs per
 //                32x32x32 step into 8 diagonal accumulators, recombined once.
+#include <algorithm>
+#include <vector>
+
 #include "limb_common.hpp"
 
 namespace spin {
@@ -84,7 +87,7 @@ __device__ inline void ring_atomic_add(u32 *p, u32 v) { atomicAdd((unsigned int 
 // The barrier at the top of iteration s also tells every wave that all R(s) are done, so stage s % 3
 // can be refilled by G(s+3).  Two groups of loads are in flight while a step computes.
 template <class T>
-__global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
+__device__ __forceinline__ void limb_gemm_body(const GemmArgs<T> &g, unsigned block)
 {
     using S = GemmShape<T>;
     constexpr int kDigits = S::ND, WM = S::WM, WN = S::WN;
@@ -96,7 +99,7 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
 
     // work item = (split, tile), tiles fastest: neighbours on an XCD work on neighbouring tiles of one k-range
     const long tiles_total = (long)g.tilesM * g.tilesN * g.n * g.batch;
-    const long item = xcd_contiguous_id(blockIdx.x, tiles_total * g.splits);
+    const long item = xcd_contiguous_id(block, tiles_total * g.splits);
     const int split = (int)(item / tiles_total);
     const TileId tile = tile_of(item % tiles_total, g.tilesM, g.tilesN);
     const int pb = tile.pb, tm = tile.tm, tn = tile.tn;
@@ -314,6 +317,20 @@ __global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
         }
 }
 
+template <class T>
+__global__ __launch_bounds__(256) void limb_gemm_kernel(GemmArgs<T> g)
+{
+    limb_gemm_body<T>(g, blockIdx.x);
+}
+
+// Products of different shapes in one launch (the grouped call): every workgroup finds its product in the table.
+template <class T>
+__global__ __launch_bounds__(256) void limb_gemm_grouped_kernel(GroupTable<GemmArgs<T>> t)
+{
+    const int gi = group_of(t, blockIdx.x);
+    limb_gemm_body<T>(t.e[gi], blockIdx.x - t.first[gi]);
+}
+
 // ------------------------------------------------- row-streaming GEMM ---
 // Z_2^64 products whose output is a single column tile (N <= 64): every left fragment would be used by
 // exactly one output tile, so writing the left operands out as fragments and reading them back (the pack
@@ -390,13 +407,13 @@ typedef __attribute__((address_space(3))) const u64x2 lds_u64x2;
 typedef __attribute__((address_space(3))) const v4i lds_v4i;
 
 template <int NP>
-__global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmArgs g)
+__device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsigned block)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int lane = threadIdx.x % 64;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
     const int rblocks = (g.M + 31) / 32;
-    const int rb = blockIdx.x % rblocks, tn = blockIdx.x / rblocks % g.tilesN, b = blockIdx.x / rblocks / g.tilesN;
+    const int rb = block % rblocks, tn = block / rblocks % g.tilesN, b = block / rblocks / g.tilesN;
     const int KT = g.KT;
     lds_char *lds3 = (lds_char *)lds;
     lds_char *e_ring = lds3 + 2 * kRawSlot;
@@ -633,6 +650,19 @@ __global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmAr
     }
 }
 
+template <int NP>
+__global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmArgs g)
+{
+    limb_gemm_rows_body<NP>(g, blockIdx.x);
+}
+
+template <int NP>
+__global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_grouped_kernel(GroupTable<RowGemmArgs> t)
+{
+    const int gi = group_of(t, blockIdx.x);
+    limb_gemm_rows_body<NP>(t.e[gi], blockIdx.x - t.first[gi]);
+}
+
 // ------------------------------------------------------------------ host ---
 struct Plan {
     int KT, nblkA, nblkB, tilesM, tilesN;
@@ -765,6 +795,130 @@ template <class T> spin_status launch_limb(const MatmulArgsT<T> &a, hipStream_t 
     return SPIN_OK;
 }
 
+// ---- grouped call: products of different shapes, a handful of launches for all of them ----------------
+// Every group gets its own fragment stores inside the workspace (the packs of all groups run before their
+// GEMMs), chooses the row-streaming or the tile kernel as a single product would, and the groups of one kind
+// share a launch: right packs (plain / stored transposed), left packs (tile-kernel groups only), row GEMMs,
+// tile GEMMs -- at most five launches per kGroupsPerLaunch groups.  Tiles are not shared between workgroups
+// here (the groups together fill the chip), so Z needs no pre-copy.
+template <class Args, class Launch> inline spin_status launch_in_tables(const std::vector<Args> &args,
+                                                                        const std::vector<unsigned> &blocks, Launch &&launch)
+{
+    for (size_t g0 = 0; g0 < args.size(); g0 += kGroupsPerLaunch) {
+        GroupTable<Args> t;
+        t.count = (int)std::min<size_t>(kGroupsPerLaunch, args.size() - g0);
+        unsigned total = 0;
+        for (int i = 0; i < t.count; ++i) {
+            t.first[i] = total;
+            t.e[i] = args[g0 + i];
+            total += blocks[g0 + i];
+        }
+        for (int i = t.count; i <= kGroupsPerLaunch; ++i) t.first[i] = total;
+        launch(t, total);
+    }
+    return SPIN_OK;
+}
+
+}  // namespace
+
+size_t limb_grouped_workspace_bytes(int n, int groups, const MatmulArgs *a)
+{
+    size_t sum = 0;
+    for (int g = 0; g < groups; ++g) sum += limb_workspace_bytes(n, a[g].batch, a[g].M, a[g].N, a[g].K);
+    return sum;
+}
+
+// Returns SPIN_ERANGE, before anything is launched, when a group cannot go into a shared launch (an inner dimension
+// that must be accumulated in several launches, or more workgroups than a grid holds); the caller then enqueues
+// the groups one after another.
+spin_status launch_matmul_limb_grouped(int n, int groups, const MatmulArgs *a, void *workspace, hipStream_t s)
+{
+    constexpr int WAVES = 4;
+    std::vector<PackArgs<u64>> left, right_plain, right_t;
+    std::vector<unsigned> left_blocks, right_plain_blocks, right_t_blocks, row_blocks, tile_blocks;
+    std::vector<RowGemmArgs> rows;
+    std::vector<GemmArgs<u64>> tiles;
+    bool vec = true;
+    char *ws = (char *)workspace;
+    for (int g = 0; g < groups; ++g) {
+        const MatmulArgs &m = a[g];
+        const Plan p = make_plan<u64>(n, m.batch, m.M, m.N, m.K);
+        if (p.KT > Ring<u64>::max_chunk_tiles) return SPIN_ERANGE;
+        vec = vec && m.K % 2 == 0;
+        char *packA = ws, *packB = ws + p.packA_bytes;
+        ws += p.packA_bytes + p.packB_bytes;
+        if (m.y_transposed) {
+            right_t.push_back(PackArgs<u64>{m.Y, m.B, packB, n, m.batch, m.N, m.K, p.nblkB, p.KT});
+            right_t_blocks.push_back(pack_left_blocks<WAVES>(p.nblkB, p.KT) * m.batch);
+        } else {
+            right_plain.push_back(PackArgs<u64>{m.Y, m.B, packB, n, m.batch, m.K, m.N, p.nblkB, p.KT});
+            right_plain_blocks.push_back(pack_right_blocks(p.nblkB, p.KT) * m.batch);
+        }
+        if (rows_kernel_applies<u64>(m, p)) {
+            rows.push_back(RowGemmArgs{m.X, m.A, packB, m.C, m.Z, m.batch, m.M, m.N, m.K, p.KT, p.tilesN});
+            row_blocks.push_back((unsigned)((long)m.batch * ceil_div(m.M, 32) * p.tilesN));
+        } else {
+            left.push_back(PackArgs<u64>{m.X, m.A, packA, n, m.batch, m.M, m.K, p.nblkA, p.KT});
+            left_blocks.push_back(pack_left_blocks<WAVES>(p.nblkA, p.KT) * m.batch);
+            tiles.push_back(GemmArgs<u64>{packA, packB, m.C, m.Z, n, m.batch, m.M, m.N, p.nblkA, p.nblkB, p.KT, 0, p.KT,
+                                          p.tilesM, p.tilesN, 1, 2 * p.KT});
+            tile_blocks.push_back((unsigned)((long)p.tilesM * p.tilesN * n * m.batch));
+        }
+    }
+    for (const std::vector<unsigned> *v : {&left_blocks, &right_plain_blocks, &right_t_blocks, &row_blocks, &tile_blocks}) {
+        unsigned long sum = 0;                           // a launch of up to kGroupsPerLaunch groups must fit a grid
+        for (unsigned b : *v) sum += b;
+        if (sum > 0x7fffffffUL) return SPIN_ERANGE;
+    }
+    spin_status st = SPIN_OK;
+    for_party_count(n, [&](auto np) {
+        constexpr int NP = decltype(np)::value;
+        {
+            KernelTimer timer(SPIN_KERNEL_PACK, s);
+            launch_in_tables(right_plain, right_plain_blocks, [&](const GroupTable<PackArgs<u64>> &t, unsigned total) {
+                pack_right_grouped_kernel<NP, u64, false><<<total, 256, 0, s>>>(t);
+            });
+            auto pack_rows = [&](const std::vector<PackArgs<u64>> &v, const std::vector<unsigned> &blocks, auto right_c) {
+                constexpr bool RIGHT = decltype(right_c)::value;
+                launch_in_tables(v, blocks, [&](const GroupTable<PackArgs<u64>> &t, unsigned total) {
+                    if (vec) pack_left_grouped_kernel<NP, u64, true, WAVES, RIGHT, false><<<total, 64 * WAVES, 0, s>>>(t);
+                    else pack_left_grouped_kernel<NP, u64, false, WAVES, RIGHT, false><<<total, 64 * WAVES, 0, s>>>(t);
+                });
+            };
+            pack_rows(right_t, right_t_blocks, std::true_type());
+            pack_rows(left, left_blocks, std::false_type());
+            st = check_launch("spin_beaver_matmul_grouped(pack)");
+            if (st != SPIN_OK) return;
+        }
+        if (!rows.empty()) {
+            constexpr int RP = NP <= 3 ? NP : 3;             // groups reach the row kernel only when n <= 3
+            static OncePerDevice lds_allowed;
+            auto kernel = limb_gemm_rows_grouped_kernel<RP>;
+            st = allow_dynamic_lds((const void *)kernel, kRowLds, lds_allowed);
+            if (st != SPIN_OK) return;
+            KernelTimer timer(SPIN_KERNEL_GEMM_LIMB, s);
+            launch_in_tables(rows, row_blocks, [&](const GroupTable<RowGemmArgs> &t, unsigned total) {
+                kernel<<<total, 64 * (RP + 1), kRowLds, s>>>(t);
+            });
+            st = check_launch("spin_beaver_matmul_grouped(row gemm)");
+            if (st != SPIN_OK) return;
+        }
+        if (!tiles.empty()) {
+            static OncePerDevice lds_allowed;
+            auto kernel = limb_gemm_grouped_kernel<u64>;
+            st = allow_dynamic_lds((const void *)kernel, GemmShape<u64>::lds_bytes, lds_allowed);
+            if (st != SPIN_OK) return;
+            KernelTimer timer(SPIN_KERNEL_GEMM_LIMB, s);
+            launch_in_tables(tiles, tile_blocks, [&](const GroupTable<GemmArgs<u64>> &t, unsigned total) {
+                kernel<<<total, 256, GemmShape<u64>::lds_bytes, s>>>(t);
+            });
+            st = check_launch("spin_beaver_matmul_grouped(tile gemm)");
+        }
+    });
+    return st;
+}
+
+namespace {
 }  // namespace
 
 size_t limb_workspace_bytes(int n, int batch, int M, int N, int K)

@@ -93,19 +93,19 @@ template <class T> struct PackArgs {
 // columns x 16 k (half a k-tile of two adjacent column blocks): every wave-wide load is one contiguous
 // 64-element row segment, every store two contiguous half-fragment chunks; consecutive waves continue
 // along the row.
+// `block` is the workgroup's index within its batch entry b.
 template <int NP, class T, bool NT>
-__global__ __launch_bounds__(256) void pack_right_kernel(PackArgs<T> a)
+__device__ __forceinline__ void pack_right_body(const PackArgs<T> &a, long block, int b)
 {
     constexpr int ND = sizeof(T);
     constexpr bool KEEP = sizeof(T) <= 8;
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int nblk2 = (a.nblk + 1) / 2;                    // pairs of column blocks
-    const long tile = (long)blockIdx.x * 4 + wave;         // (kt, half, block pair), block pair fastest
+    const long tile = block * 4 + wave;                    // (kt, half, block pair), block pair fastest
     if (tile >= (long)nblk2 * a.KT * 2) return;
     const int blk2 = (int)(tile % nblk2);
     const int half = (int)(tile / nblk2 % 2), kt = (int)(tile / nblk2 / 2);
     const int blk = blk2 * 2 + lane / 32;
-    const int b = blockIdx.z;
     const int K = a.rows, N = a.cols;
     const int col = blk2 * 64 + lane;
     const int k0 = kt * 32 + 16 * half;
@@ -169,6 +169,37 @@ __global__ __launch_bounds__(256) void pack_right_kernel(PackArgs<T> a)
     }
     if (owns) store_digit_rows<T, NT>(w, frag(1));
 }
+__host__ __device__ inline unsigned pack_right_blocks(int nblk, int KT) { return (unsigned)(((long)((nblk + 1) / 2) * KT * 2 + 3) / 4); }
+
+template <int NP, class T, bool NT>
+__global__ __launch_bounds__(256) void pack_right_kernel(PackArgs<T> a)
+{
+    pack_right_body<NP, T, NT>(a, blockIdx.x, blockIdx.z);
+}
+
+// Several products of different shapes in one launch (the grouped call): the descriptors travel as a kernel
+// argument, every workgroup looks its group up from the table of first workgroup ids.
+constexpr int kGroupsPerLaunch = 32;
+template <class Args> struct GroupTable {
+    int count;
+    unsigned first[kGroupsPerLaunch + 1];                  // first workgroup id of every group, then the total
+    Args e[kGroupsPerLaunch];
+};
+template <class Args> __device__ inline int group_of(const GroupTable<Args> &t, unsigned id)
+{
+    int g = 0;
+    for (int i = 1; i < t.count; ++i) g += id >= t.first[i] ? 1 : 0;
+    return g;
+}
+
+template <int NP, class T, bool NT>
+__global__ __launch_bounds__(256) void pack_right_grouped_kernel(GroupTable<PackArgs<T>> t)
+{
+    const int gi = group_of(t, blockIdx.x);
+    const PackArgs<T> a = t.e[gi];
+    const unsigned local = blockIdx.x - t.first[gi], per_batch = pack_right_blocks(a.nblk, a.KT);
+    pack_right_body<NP, T, NT>(a, local % per_batch, (int)(local / per_batch));
+}
 
 // Left side: source M x K row-major, a fragment row is a matrix row.  Reading 16 consecutive k per
 // lane directly would make every wave-wide load touch 64 different rows; instead a wave reads its
@@ -180,7 +211,7 @@ __global__ __launch_bounds__(256) void pack_right_kernel(PackArgs<T> a)
 // Q.K^T): the access pattern is the left side's, the slot rule the right side's (party 0's slot holds
 // B_0 + F).
 template <int NP, class T, bool VEC, int WAVES, bool RIGHT, bool NT>
-__global__ __launch_bounds__(64 * WAVES) void pack_left_kernel(PackArgs<T> a)
+__device__ __forceinline__ void pack_left_body(const PackArgs<T> &a, long block, int b)
 {
     constexpr int ND = sizeof(T);
     constexpr bool KEEP = sizeof(T) <= 8;
@@ -192,11 +223,10 @@ __global__ __launch_bounds__(64 * WAVES) void pack_left_kernel(PackArgs<T> a)
     struct alignas(16) Pair { T e[EPL]; };
     __shared__ __attribute__((aligned(16))) char turn[WAVES][32 * kRowBytes];
     const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
-    long tile = (long)blockIdx.x * WAVES + wave;            // (blk, kt) pair
+    long tile = block * WAVES + wave;                       // (blk, kt) pair
     const bool active = tile < (long)a.nblk * a.KT;
     if (!active) tile = 0;
     const int blk = (int)(tile / a.KT), kt = (int)(tile % a.KT);
-    const int b = blockIdx.z;
     const int M = a.rows, K = a.cols;
     const size_t mat = (size_t)M * K;
     const size_t party_stride = (size_t)a.batch * mat;
@@ -307,6 +337,22 @@ __global__ __launch_bounds__(64 * WAVES) void pack_left_kernel(PackArgs<T> a)
         turn_and_store(tv, frag(1));
     }
 }
+template <int WAVES> __host__ __device__ inline unsigned pack_left_blocks(int nblk, int KT) { return (unsigned)(((long)nblk * KT + WAVES - 1) / WAVES); }
+
+template <int NP, class T, bool VEC, int WAVES, bool RIGHT, bool NT>
+__global__ __launch_bounds__(64 * WAVES) void pack_left_kernel(PackArgs<T> a)
+{
+    pack_left_body<NP, T, VEC, WAVES, RIGHT, NT>(a, blockIdx.x, blockIdx.z);
+}
+
+template <int NP, class T, bool VEC, int WAVES, bool RIGHT, bool NT>
+__global__ __launch_bounds__(64 * WAVES) void pack_left_grouped_kernel(GroupTable<PackArgs<T>> t)
+{
+    const int gi = group_of(t, blockIdx.x);
+    const PackArgs<T> a = t.e[gi];
+    const unsigned local = blockIdx.x - t.first[gi], per_batch = pack_left_blocks<WAVES>(a.nblk, a.KT);
+    pack_left_body<NP, T, VEC, WAVES, RIGHT, NT>(a, local % per_batch, (int)(local / per_batch));
+}
 
 // One direct-to-LDS load: 64 lanes x 16 bytes from src + lane*16 to the LDS address lds_dst + lane*16.
 // Issued through inline assembly so that the compiler's LDS-DMA bookkeeping does not serialise the
@@ -376,7 +422,7 @@ inline void launch_pack_left(const MatmulArgsT<T> &a, char *packA, int nblkA, in
         constexpr int NP = decltype(np)::value;
         for_pack_streaming<T>(a.n, a.batch, a.M, a.K, [&](auto nt) {
             constexpr bool NT = decltype(nt)::value;
-            dim3 ga((unsigned)(((long)nblkA * KT + WAVES - 1) / WAVES), 1, a.batch);
+            dim3 ga(pack_left_blocks<WAVES>(nblkA, KT), 1, a.batch);
             if (vec) pack_left_kernel<NP, T, true, WAVES, false, NT><<<ga, 64 * WAVES, 0, s>>>(pa);
             else pack_left_kernel<NP, T, false, WAVES, false, NT><<<ga, 64 * WAVES, 0, s>>>(pa);
         });
@@ -395,12 +441,12 @@ inline void launch_pack_right(const MatmulArgsT<T> &a, char *packB, int nblkB, i
             constexpr bool NT = decltype(nt)::value;
             if (a.y_transposed) {                        // Y, B stored [N][K]: rows of the source are fragment rows
                 PackArgs<T> pb{a.Y, a.B, packB, a.n, a.batch, a.N, a.K, nblkB, KT};
-                dim3 gb((unsigned)(((long)nblkB * KT + WAVES - 1) / WAVES), 1, a.batch);
+                dim3 gb(pack_left_blocks<WAVES>(nblkB, KT), 1, a.batch);
                 if (vec) pack_left_kernel<NP, T, true, WAVES, true, NT><<<gb, 64 * WAVES, 0, s>>>(pb);
                 else pack_left_kernel<NP, T, false, WAVES, true, NT><<<gb, 64 * WAVES, 0, s>>>(pb);
             } else {
                 PackArgs<T> pb{a.Y, a.B, packB, a.n, a.batch, a.K, a.N, nblkB, KT};
-                dim3 gb((unsigned)(((long)((nblkB + 1) / 2) * KT * 2 + 3) / 4), 1, a.batch);
+                dim3 gb(pack_right_blocks(nblkB, KT), 1, a.batch);
                 pack_right_kernel<NP, T, NT><<<gb, 256, 0, s>>>(pb);
             }
         });

@@ -196,13 +196,15 @@ spin_status spin_beaver_matmul_nt(int n, int batch, int M, int N, int K, const u
 size_t spin_beaver_matmul_grouped_workspace_bytes(int n, int groups, const spin_matmul_group *desc, int path)
 {
     if (desc == nullptr || groups < 1 || groups > SPIN_MAX_GROUPS) return 0;
-    size_t need = 0;
+    size_t largest = 0, sum = 0;
     for (int g = 0; g < groups; ++g) {
         const size_t b = spin_beaver_matmul_workspace_bytes(n, desc[g].batch, desc[g].M, desc[g].N, desc[g].K, path);
         if (b == 0) return 0;
-        if (b > need) need = b;
+        if (b > largest) largest = b;
+        sum += b;
     }
-    return need;
+    // the limb path packs every group before the first GEMM runs, so all fragment stores exist at once
+    return path == SPIN_GEMM_LIMB_MFMA ? sum : largest;
 }
 
 spin_status spin_beaver_matmul_grouped(int n, int groups, const spin_matmul_group *desc, int path,
@@ -219,6 +221,15 @@ spin_status spin_beaver_matmul_grouped(int n, int groups, const spin_matmul_grou
     const size_t need = spin_beaver_matmul_grouped_workspace_bytes(n, groups, desc, path);
     if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0 || need == 0 || workspace_bytes < need)
         return SPIN_EWORKSPACE;
+    if (path == SPIN_GEMM_LIMB_MFMA) {
+        MatmulArgs args[SPIN_MAX_GROUPS];
+        for (int g = 0; g < groups; ++g) {
+            const spin_matmul_group &d = desc[g];
+            args[g] = MatmulArgs{n, d.batch, d.M, d.N, d.K, d.X, d.Y, d.A, d.B, d.C, d.Z, nullptr, d.y_transposed != 0};
+        }
+        const spin_status st = launch_matmul_limb_grouped(n, groups, args, workspace, (hipStream_t)stream);
+        if (st != SPIN_ERANGE) return st;                // SPIN_ERANGE: a group does not fit a shared launch, nothing was launched
+    }
     for (int g = 0; g < groups; ++g) {
         const spin_matmul_group &d = desc[g];
         spin_status st = beaver_matmul64(n, d.batch, d.M, d.N, d.K, d.X, d.Y, d.A, d.B, d.C, d.Z, path, workspace,

@@ -165,7 +165,10 @@ def test_validation_of_the_grouped_matmul(L):
         d.X = d.Y = d.A = d.B = d.C = d.Z = fake
     ws = ctypes.c_void_p(0x10000)
     f, q = L.spin_beaver_matmul_grouped, L.spin_beaver_matmul_grouped_workspace_bytes
-    assert q(2, 2, desc, 0) == L.spin_beaver_matmul_workspace_bytes(2, 1, 8, 8, 8, 0)
+    # limb path: every group has its own fragment stores (the packs of all groups run before the GEMMs); the
+    # baseline path runs the groups one after another on one workspace
+    assert q(2, 2, desc, 0) == 2 * L.spin_beaver_matmul_workspace_bytes(2, 1, 8, 8, 8, 0)
+    assert q(2, 2, desc, 1) == L.spin_beaver_matmul_workspace_bytes(2, 1, 8, 8, 8, 1)
     assert f(2, 0, desc, 0, ws, 1 << 30, None) == EINVAL
     assert f(2, 65, desc, 0, ws, 1 << 30, None) == EINVAL
     assert f(2, 2, None, 0, ws, 1 << 30, None) == EINVAL

@@ -155,11 +155,14 @@ def test_downsized_order_with_the_factor_tiled_inside_the_kernel():
 @pytest.mark.parametrize("path", [pytest.param(spin.LIMB_MFMA, id="limb"), pytest.param(spin.VALU, id="valu")])
 def test_grouped_matmuls_of_different_shapes_in_one_call(path):
     # the attention products of three LeViT-like stages (196, 49 and 16 tokens) in one call: Q.K^T with K
-    # stored untransposed, then P.V; every group against the oracle
+    # stored untransposed, then P.V; plus products that take the tile kernel (long inner dimension, many column
+    # tiles), an odd inner dimension and a 1 x 1 x 1 product.  Every group against the oracle, and against the
+    # same products submitted one call at a time (on the limb path the grouped call shares launches).
     n = 3
     rng = np.random.default_rng(77)
     shapes = [(4, 196, 196, 64, True), (4, 196, 64, 196, False), (8, 49, 49, 32, True), (8, 49, 32, 49, False),
-              (12, 16, 16, 32, True), (1, 1, 1, 1, False)]
+              (12, 16, 16, 32, True), (1, 1, 1, 1, False), (1, 130, 200, 1030, False), (2, 70, 150, 999, True),
+              (1, 300, 64, 40, False)]
     groups, wants = [], []
     for idx, (batch, M, N, K, yt) in enumerate(shapes):
         X = rng.integers(0, 1 << 64, size=(n, batch, M, K), dtype=np.uint64)
@@ -170,5 +173,34 @@ def test_grouped_matmuls_of_different_shapes_in_one_call(path):
             Y, B = np.ascontiguousarray(Y.transpose(0, 1, 3, 2)), np.ascontiguousarray(B.transpose(0, 1, 3, 2))
         groups.append({"X": dev(X), "Y": dev(Y), "A": dev(A), "B": dev(B), "C": dev(C), "y_transposed": yt})
     outs = spin.beaver_matmul_grouped(groups, path=path)
-    for z, want in zip(outs, wants):
+    for z, want, g in zip(outs, wants, groups):
+        assert (host(z) == want).all()
+        single = spin.beaver_matmul(g["X"], g["Y"], g["A"], g["B"], g["C"], path=path, y_transposed=g["y_transposed"])
+        assert torch.equal(z, single)
+    # in place on C, and a second call on the same workspace
+    ws = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    for g in groups:
+        g["out"] = g["C"]
+    spin.beaver_matmul_grouped(groups, path=path, workspace=ws)
+    for g, want in zip(groups, wants):
+        assert (host(g["C"]) == want).all()
+
+
+def test_more_groups_than_one_launch_table_holds():
+    # 40 groups of five different shapes and 2 parties: the descriptor tables are sent 32 groups at a time
+    n = 2
+    rng = np.random.default_rng(78)
+    base = [(1, 33, 70, 34, False), (2, 64, 64, 64, True), (1, 100, 31, 96, False), (3, 17, 130, 20, True), (1, 128, 128, 250, False)]
+    groups, wants = [], []
+    for idx in range(40):
+        batch, M, N, K, yt = base[idx % 5]
+        M += idx // 5
+        X = rng.integers(0, 1 << 64, size=(n, batch, M, K), dtype=np.uint64)
+        Y = rng.integers(0, 1 << 64, size=(n, batch, K, N), dtype=np.uint64)
+        A, B, C = oracle.dealer_matmul(n, batch, M, N, K, seed=900 + idx)
+        wants.append(oracle.beaver_matmul(X, Y, A, B, C))
+        if yt:
+            Y, B = np.ascontiguousarray(Y.transpose(0, 1, 3, 2)), np.ascontiguousarray(B.transpose(0, 1, 3, 2))
+        groups.append({"X": dev(X), "Y": dev(Y), "A": dev(A), "B": dev(B), "C": dev(C), "y_transposed": yt})
+    for z, want in zip(spin.beaver_matmul_grouped(groups), wants):
         assert (host(z) == want).all()
