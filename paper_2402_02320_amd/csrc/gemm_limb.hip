@@ -76,6 +76,24 @@ struct GemmShape {
     static_assert(ND * WM * WN * 16 <= 256, "accumulators exceed the AGPR file");
 };
 
+// sum_d D_d 256^d (mod 2^(8 ND)) of the diagonal sums D_d held as int32: the low four diagonals as signed
+// 64-bit multiply-adds (256^d fits an int32), the high four only reach the upper word, where they are plain
+// 32-bit shifts and adds.  About ten instructions per element where shifting every sign-extended term
+// through 64 bits takes forty.
+__device__ inline u64 recombine_diagonals(int d0, int d1, int d2, int d3, int d4, int d5, int d6, int d7)
+{
+    long long low = (long long)d0;
+    low += (long long)d1 * (1 << 8);
+    low += (long long)d2 * (1 << 16);
+    low += (long long)d3 * (1 << 24);
+    const u32 high = (u32)((u64)low >> 32) + (u32)d4 + ((u32)d5 << 8) + ((u32)d6 << 16) + ((u32)d7 << 24);
+    return ((u64)high << 32) | (u32)low;
+}
+__device__ inline u32 recombine_diagonals(int d0, int d1, int d2, int d3)
+{
+    return (u32)d0 + ((u32)d1 << 8) + ((u32)d2 << 16) + ((u32)d3 << 24);
+}
+
 __device__ inline void ring_atomic_add(u64 *p, u64 v) { atomicAdd((unsigned long long *)p, (unsigned long long)v); }
 __device__ inline void ring_atomic_add(u32 *p, u32 v) { atomicAdd((unsigned int *)p, (unsigned int)v); }
 
@@ -299,9 +317,14 @@ __device__ __forceinline__ void limb_gemm_body(const GemmArgs<T> &g, unsigned bl
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-#pragma unroll
-                for (int d = 0; d < kDigits; ++d) v[r] += (T)(int64_t)acc[i][j][d][r] << (8 * d);
+            for (int r = 0; r < 16; ++r) {
+                if constexpr (kDigits == 8)
+                    v[r] += recombine_diagonals(acc[i][j][0][r], acc[i][j][1][r], acc[i][j][2][r], acc[i][j][3][r],
+                                                acc[i][j][4 % kDigits][r], acc[i][j][5 % kDigits][r],
+                                                acc[i][j][6 % kDigits][r], acc[i][j][7 % kDigits][r]);
+                else
+                    v[r] += recombine_diagonals(acc[i][j][0][r], acc[i][j][1][r], acc[i][j][2][r], acc[i][j][3][r]);
+            }
             if (atomic) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
@@ -637,8 +660,8 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-#pragma unroll
-            for (int d = 0; d < 8; ++d) v[r] += (u64)(int64_t)acc[j][d][r] << (8 * d);
+            v[r] += recombine_diagonals(acc[j][0][r], acc[j][1][r], acc[j][2][r], acc[j][3][r], acc[j][4][r], acc[j][5][r],
+                                        acc[j][6][r], acc[j][7][r]);
         if (interior) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) Zm[(size_t)row_of(r) * g.N + col] = v[r];
