@@ -61,17 +61,17 @@ def parse():
 
 
 def measured_traffic(kernel, cfg):
-    """HBM-side bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE and WRITE_SIZE
+    """HBM-side bytes per launch from the committed rocprofv3 counter summaries (FETCH_SIZE and WRITE_SIZE
     passes, calibrated against a plain copy), or None where no summary covers this kernel and workload."""
-    path = os.path.join(ROOT, "profiles", "config%d_step_hbm_traffic.txt" % cfg)
-    try:
-        for line in open(path):
-            parts = line.split()
-            if len(parts) == 4 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel \
-                    and parts[2] == "config%d" % cfg:
-                return int(parts[3])
-    except OSError:
-        pass
+    want = ["traffic_bytes_per_launch", kernel, "config%d" % cfg]
+    for name in sorted(os.listdir(os.path.join(ROOT, "profiles"))) if os.path.isdir(os.path.join(ROOT, "profiles")) else []:
+        try:
+            for line in open(os.path.join(ROOT, "profiles", name)):
+                parts = line.split()
+                if len(parts) == 4 and parts[:3] == want:
+                    return int(parts[3])
+        except OSError:
+            pass
     return None
 
 
@@ -377,6 +377,7 @@ def run_config(args, cfg):
     gemm_z = []                    # Z of every GEMM leg
     ws_bytes = 0
     gemm_plans = []
+    all_rows = True
     for gi, g in enumerate(c.gemms):
         Xr, Yr = workloads.gemm_plaintexts(cfg, gi)
         batch, M, K = Xr.shape
@@ -418,7 +419,9 @@ def run_config(args, cfg):
         ring_macs += 2.0 * n * batch * M * N * K
         count_bytes("share", (1 + n) * 8.0 * (szB + (0 if chained else szA)))
         count_bytes("trunc", 5 * n * 8.0 * szC)
-        fused_left = path == spin.LIMB_MFMA and N <= 64 and n <= 3 and K % 2 == 0   # left fragments built in the GEMM
+        # left fragments built inside the GEMM (the library's own rule also weighs a cost model; these shapes pass it)
+        fused_left = path == spin.LIMB_MFMA and n <= 3 and K % 2 == 0 and (N <= 64 or (N <= 128 and K <= 128))
+        all_rows = all_rows and fused_left
         count_bytes("pack", 8.0 * (3 * n + 1) * (szB + (0 if fused_left else szA)))
         legs.append("%sBeaver matmul %s batch %d M=%d N=%d K=%d (%s) + trunc"
                     % ("" if chained else "share X, ", g.name, batch, M, N, K,
@@ -540,11 +543,14 @@ def run_config(args, cfg):
         # all GEMM launches of a step together: algorithmic int8 operations / their summed kernel time
         achieved = ring_macs * INT8_OPS_PER_RING_MAC / (gemm_ms_per_step * 1e-3) / 1e12
         with_pack = ring_macs * INT8_OPS_PER_RING_MAC / ((gemm_ms + pack_ms) / args.steps * 1e-3) / 1e12
-        traffic = measured_traffic("limb_gemm_kernel", cfg)
-        roofline = {"bound": "mfma", "kernel": "limb_gemm_kernel", "achieved": achieved, "peak": PEAK_INT8_TOPS,
+        # which GEMM kernel the library picks: the row-streaming one for products of few column tiles, at most
+        # three parties and an even inner dimension (it builds the left fragments itself), else the tile kernel
+        kernel_name = "limb_gemm_rows_kernel" if all_rows else "limb_gemm_kernel"
+        traffic = measured_traffic(kernel_name, cfg)
+        roofline = {"bound": "mfma", "kernel": kernel_name, "achieved": achieved, "peak": PEAK_INT8_TOPS,
                     "unit": "TOP/s", "frac": achieved / PEAK_INT8_TOPS, "traffic": traffic,
-                    "traffic_source": ("profiles/config%d_step_hbm_traffic.txt: rocprofv3 FETCH_SIZE / WRITE_SIZE of an "
-                                       "earlier run of this command, not measured in this run" % cfg) if traffic else None,
+                    "traffic_source": ("profiles/ (config %d): rocprofv3 FETCH_SIZE / WRITE_SIZE of an earlier run of "
+                                       "this command, not measured in this run" % cfg) if traffic else None,
                     "avg_launch_ms": gemm_avg_ms, "launches_per_step": launches_per_step,
                     "ring_mac_per_s": ring_macs / (gemm_ms_per_step * 1e-3),
                     "frac_with_pack": with_pack / PEAK_INT8_TOPS,
