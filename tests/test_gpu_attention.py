@@ -204,3 +204,21 @@ def test_more_groups_than_one_launch_table_holds():
         groups.append({"X": dev(X), "Y": dev(Y), "A": dev(A), "B": dev(B), "C": dev(C), "y_transposed": yt})
     for z, want in zip(spin.beaver_matmul_grouped(groups), wants):
         assert (host(z) == want).all()
+
+
+def test_grouped_call_with_five_parties_takes_the_tile_kernel_for_every_group():
+    # more than three parties: no group is eligible for the row-streaming kernel, all left operands are packed
+    n = 5
+    rng = np.random.default_rng(79)
+    shapes = [(2, 64, 64, 64, True), (1, 200, 64, 130, False), (3, 33, 129, 48, False), (1, 128, 256, 512, True)]
+    groups, wants = [], []
+    for idx, (batch, M, N, K, yt) in enumerate(shapes):
+        X = rng.integers(0, 1 << 64, size=(n, batch, M, K), dtype=np.uint64)
+        Y = rng.integers(0, 1 << 64, size=(n, batch, K, N), dtype=np.uint64)
+        A, B, C = oracle.dealer_matmul(n, batch, M, N, K, seed=950 + idx)
+        wants.append(oracle.beaver_matmul(X, Y, A, B, C))
+        if yt:
+            Y, B = np.ascontiguousarray(Y.transpose(0, 1, 3, 2)), np.ascontiguousarray(B.transpose(0, 1, 3, 2))
+        groups.append({"X": dev(X), "Y": dev(Y), "A": dev(A), "B": dev(B), "C": dev(C), "y_transposed": yt})
+    for z, want in zip(spin.beaver_matmul_grouped(groups), wants):
+        assert (host(z) == want).all()
