@@ -23,6 +23,11 @@
 //  limb_gemm_kernel  per party: Z_i = C_i + [E | A_i] . [B_i' ; F], fragments
 //                streamed global -> LDS with direct-to-LDS loads, 36 MFMAs per
 //                32x32x32 step into 8 diagonal accumulators, recombined once.
+//  limb_gemm_rows_kernel  products with few column tiles (N <= 64; attention shapes), at most three
+//                parties: no left pack at all -- a producer wave streams the raw X_j, A_j tiles into LDS
+//                and opens E, one consumer wave per party converts its A_p in registers and runs the MFMAs.
+//  *_grouped_kernel  the same bodies for several products of different shapes in one launch
+//                (spin_beaver_matmul_grouped), the products found through a table in the kernel arguments.
 #include <algorithm>
 #include <vector>
 
