@@ -618,9 +618,9 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
     using B0 = std::integral_constant<int, 0>;
     using B1 = std::integral_constant<int, 1>;
 
-    workgroup_barrier();                                 // raw tiles 0 and 1 and E(0) are in LDS
 #pragma unroll
-    for (int q = 0; q < 16; ++q) fr[1][q] = right_fragment(q, f_rsrc, 0);
+    for (int q = 0; q < 16; ++q) fr[1][q] = right_fragment(q, f_rsrc, 0);   // in flight while the producer starts up
+    workgroup_barrier();                                 // raw tiles 0 and 1 and E(0) are in LDS
 #pragma unroll
     for (int c = 0; c < 4; ++c)
 #pragma unroll
