@@ -284,22 +284,35 @@ __device__ __forceinline__ void limb_gemm_body(const GemmArgs<T> &g, unsigned bl
         iteration(B1(), F(), Y(), Y());
     }
     iteration(B0(), F(), Y(), F());                       // step steps-2
-    iteration(B1(), F(), F(), F());                       // step steps-1
 
-    // Recombine the diagonals and add C_i.  The 16 C values of a lane in one MFMA tile are loaded before
-    // the first of its stores: interleaved, every load would wait out the store before it (C and Z may
-    // be the same buffer, so the compiler keeps their order), 32 memory round trips in a row with
-    // nothing else on the CU.
-    // Tiles that lie wholly inside the matrix take branch-free loads and stores: with a bounds check per
-    // element every store sits in a basic block of its own and again waits for the one before.  Only
-    // the memory accesses are duplicated; the arithmetic between them is shared by both cases.
+    // C_i is fetched under the last step (the fragment buffer that step would have filled is free), so that
+    // the epilogue starts with its operands at hand instead of a memory round trip with nothing else on the
+    // CU.  Rows and columns beyond the matrix are redirected to its last row / column; what they bring is
+    // never stored.  C and Z may be the same buffer: every element is read and written by the same lane.
+    // With several workgroups per tile (splits > 1) Z already holds C and every part is added atomically:
+    // ring addition is associative and commutative, so the result does not depend on the order of arrival.
     const size_t mat = (size_t)g.M * g.N;
     const T *Cm = g.C + (size_t)pb * mat;
     T *Zm = g.Z + (size_t)pb * mat;
     const bool interior = (tm + 1) * S::BM <= g.M && (tn + 1) * S::BN <= g.N;     // uniform over the workgroup
-    // With several workgroups per tile (splits > 1) Z already holds C and every part is added atomically:
-    // ring addition is associative and commutative, so the result does not depend on the order of arrival.
     const bool atomic = g.splits > 1;
+    T cv[WM][WN][16];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            const int col = min(tn * S::BN + (wn * WN + j) * 32 + lane % 32, g.N - 1);
+            const int row0 = tm * S::BM + (wm * WM + i) * 32 + 4 * (lane / 32);
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                cv[i][j][r] = atomic ? (T)0 : Cm[(size_t)min(row0 + 8 * (r / 4) + r % 4, g.M - 1) * g.N + col];
+        }
+    __builtin_amdgcn_sched_barrier(0);
+    iteration(B1(), F(), F(), F());                       // step steps-1
+
+    // Recombine the diagonals and add C_i.
+    // Tiles that lie wholly inside the matrix take branch-free stores: with a bounds check per element every
+    // store sits in a basic block of its own and waits for the one before.
 #pragma unroll
     for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -309,18 +322,8 @@ __device__ __forceinline__ void limb_gemm_body(const GemmArgs<T> &g, unsigned bl
             auto row_of = [&](int r) { return row0 + 8 * (r / 4) + r % 4; };
             T v[16];
             __builtin_amdgcn_sched_barrier(0);           // keeps the scheduler from hoisting the next tile's work
-            if (atomic) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) v[r] = 0;
-            } else if (interior) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) v[r] = Cm[(size_t)row_of(r) * g.N + col];
-            } else {
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    v[r] = (row_of(r) < g.M && col < g.N) ? Cm[(size_t)row_of(r) * g.N + col] : (T)0;
-            }
-            __builtin_amdgcn_sched_barrier(0);
+            for (int r = 0; r < 16; ++r) v[r] = cv[i][j][r];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 if constexpr (kDigits == 8)
@@ -639,30 +642,36 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
     }
     koff = (u32)(KT - 1) * (8 * kFrag);                  // restated from the argument, so that it stays scalar
     half_step(B1(), Y(), b_rsrc, koff, e_ring + ((KT - 1) % 2) * (8 * kFrag));
-    half_step(B0(), F(), f_rsrc, koff, a_raw);
-    workgroup_barrier();
 
-    // recombine the diagonals, add C_p, store (same structure as the tile kernel's epilogue)
+    // C_p is fetched under the last half step (the fragment buffer that half step would have filled is free):
+    // the epilogue then starts with its operands at hand.  Rows and columns beyond the matrix are redirected
+    // to its last row / column; what they bring is never stored.  C may be Z itself: every element is read
+    // and written by the same lane of the same workgroup.
     const size_t zmat = (size_t)g.M * g.N;
     const u64 *Cm = g.C + ((size_t)party * g.batch + b) * zmat;
     u64 *Zm = g.Z + ((size_t)party * g.batch + b) * zmat;
     const bool interior = (rb + 1) * 32 <= g.M && (tn + 1) * 64 <= g.N;
+    const int row0 = rb * 32 + 4 * (lane / 32);
+    auto row_of = [&](int r) { return row0 + 8 * (r / 4) + r % 4; };
+    u64 cv[2][16];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int col = min(tn * 64 + j * 32 + lane % 32, g.N - 1);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) cv[j][r] = Cm[(size_t)min(row_of(r), g.M - 1) * g.N + col];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    half_step(B0(), F(), f_rsrc, koff, a_raw);
+    workgroup_barrier();
+
+    // recombine the diagonals, add C_p, store (same structure as the tile kernel's epilogue)
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int col = tn * 64 + j * 32 + lane % 32;
-        const int row0 = rb * 32 + 4 * (lane / 32);
-        auto row_of = [&](int r) { return row0 + 8 * (r / 4) + r % 4; };
         u64 v[16];
         __builtin_amdgcn_sched_barrier(0);
-        if (interior) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) v[r] = Cm[(size_t)row_of(r) * g.N + col];
-        } else {
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                v[r] = (row_of(r) < g.M && col < g.N) ? Cm[(size_t)row_of(r) * g.N + col] : 0;
-        }
-        __builtin_amdgcn_sched_barrier(0);
+        for (int r = 0; r < 16; ++r) v[r] = cv[j][r];
 #pragma unroll
         for (int r = 0; r < 16; ++r)
             v[r] += recombine_diagonals(acc[j][0][r], acc[j][1][r], acc[j][2][r], acc[j][3][r], acc[j][4][r], acc[j][5][r],
