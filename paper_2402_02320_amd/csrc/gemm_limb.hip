@@ -384,8 +384,9 @@ __global__ __launch_bounds__(256) void limb_gemm_grouped_kernel(GroupTable<GemmA
 // element, and what they bring only meets zero-padded rows of the right fragments (k >= K) or lands in
 // output rows that are never stored (row >= M).
 // Synchronisation: one workgroup barrier per k-tile.  In iteration g the consumers read E(g) from ring
-// stage g % 2 (first half) and raw A_p(g+1) from raw slot (g+1) % 2 (second half); the producer reads raw
-// slot (g+1) % 2, writes E(g+1) to stage (g+1) % 2 and refills raw slot g % 2 with k-tile g + 2.
+// stage g % 2 (first half) and raw A_p(g+1) from raw slot (g+1) % 3 (second half); the producer reads raw
+// slot (g+1) % 3, writes E(g+1) to stage (g+1) % 2, refills raw slot g % 3 with k-tile g + 3 and waits for
+// k-tile g + 2, issued one iteration earlier: every load has two iterations to arrive.
 struct RowGemmArgs {
     const u64 *X, *A;        // [n][batch][M][K]
     const char *packB;       // right fragment store [n+1][batch][2 tilesN][KT][8][1024]: slot 0 = F, 1 + i = B_i'
@@ -400,7 +401,8 @@ struct RowGemmArgs {
 // 4 rows x 256 bytes with whole 128-byte lines of memory.
 constexpr int kRawTile = 32 * 32 * 8;
 constexpr int kRawSlot = 3 * 2 * kRawTile;               // X_j then A_j for up to three parties
-constexpr int kRowLds = 2 * kRawSlot + 2 * 8 * kFrag;    // two raw slots, two stages of E fragments
+constexpr int kRawSlots = 3;                             // raw k-tiles in LDS: one in use, two in flight
+constexpr int kRowLds = kRawSlots * kRawSlot + 2 * 8 * kFrag;    // + two stages of E fragments: all 160 KB of the CU
 
 // 16 direct-to-LDS loads: the 8 chunks of X_j's and A_j's raw tile.  m0 (LDS base of each load) is put
 // back afterwards; the scalar add that sets it clobbers scc.
@@ -447,7 +449,7 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
     const int rb = block % rblocks, tn = block / rblocks % g.tilesN, b = block / rblocks / g.tilesN;
     const int KT = g.KT;
     lds_char *lds3 = (lds_char *)lds;
-    lds_char *e_ring = lds3 + 2 * kRawSlot;
+    lds_char *e_ring = lds3 + kRawSlots * kRawSlot;
     // this lane's 16 consecutive k of row lane % 32, half lane / 32, in a raw tile: piece q at raw_lane ^ (16 q)
     const u32 raw_lane = (2 * (lane % 32) + lane / 32) * 128 + (lane % 8) * 16;
 
@@ -470,8 +472,8 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
         const size_t tile0 = ((size_t)b * g.M + (size_t)rb * 32) * row_pitch;     // party 0, k-tile 0
         const size_t party_stride = (size_t)g.batch * g.M * row_pitch;
         const u32 raw0 = (u32)(uintptr_t)lds3;
-        auto issue = [&](int kt) {                       // all parties' tiles of k-tile kt -> raw slot kt % 2
-            const u32 dst = raw0 + (kt % 2) * kRawSlot;
+        auto issue = [&](int kt) {                       // all parties' tiles of k-tile kt -> raw slot kt % 3
+            const u32 dst = raw0 + (kt % kRawSlots) * kRawSlot;
             const bool last = k_edge && kt + 1 == KT;
 #pragma unroll
             for (int j = 0; j < NP; ++j) {
@@ -480,8 +482,8 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
                 else load_raw_pair((const char *)g.X + off, (const char *)g.A + off, dst + j * (2 * kRawTile), voff);
             }
         };
-        auto open_tile = [&](int kt) {                   // E(kt) from raw slot kt % 2 -> fragment stage kt % 2
-            lds_char *slot = lds3 + (kt % 2) * kRawSlot;
+        auto open_tile = [&](int kt) {                   // E(kt) from raw slot kt % 3 -> fragment stage kt % 2
+            lds_char *slot = lds3 + (kt % kRawSlots) * kRawSlot;
             u64x2 opened[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) opened[q] = (u64x2)(0);
@@ -499,20 +501,31 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
                 w[2 * q] = to_digits<u64>(opened[q].x);
                 w[2 * q + 1] = to_digits<u64>(opened[q].y);
             }
-            store_digit_rows<u64>(w, lds + 2 * kRawSlot + (kt % 2) * (8 * kFrag) + lane * 16);
+            store_digit_rows<u64>(w, lds + kRawSlots * kRawSlot + (kt % 2) * (8 * kFrag) + lane * 16);
+        };
+        // Two k-tiles are in flight while one is in use.  Loads return in order, so waiting until at most one
+        // k-tile's loads (16 NP) are outstanding means that everything older has landed; before a k-tile is
+        // issued the count is brought down to 15, which keeps it within the wave's 6-bit counter.
+        auto issue_ahead = [&](int kt) {                 // issue k-tile kt (if any); on return every older one has landed
+            if (kt < KT) {
+                wait_loads<15>();
+                issue(kt);
+                wait_loads<16 * NP>();
+            } else {
+                wait_loads<0>();
+            }
         };
         issue(0);
         wait_loads<0>();
         if (KT > 1) issue(1);
         open_tile(0);
-        wait_loads<0>();
+        issue_ahead(2);
         wait_lds();
         workgroup_barrier();                             // raw tiles 0 and 1 and E(0) are in LDS
         workgroup_barrier();                             // the consumers have taken A_p(0) out of raw slot 0
-        for (int kt = 0; kt < KT; ++kt) {
-            if (kt + 2 < KT) issue(kt + 2);
+        for (int kt = 0; kt < KT; ++kt) {                // the barrier that ends iteration kt: raw tile kt + 2 and E(kt + 1) are in LDS
             if (kt + 1 < KT) open_tile(kt + 1);
-            wait_loads<0>();
+            issue_ahead(kt + 3);                         // into the slot of k-tile kt, which nobody reads any more
             wait_lds();
             workgroup_barrier();
         }
@@ -632,11 +645,13 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
     workgroup_barrier();                                 // raw slot 0 may be refilled
     u32 koff = 0;                                        // byte offset of the current k-tile in a fragment stream
     u32 par = 0;                                         // kt % 2
+    u32 slot = 0;                                        // kt % 3
     for (int kt = 0; kt + 1 < KT; ++kt) {                // the last k-tile is peeled: no branch around MFMAs
         half_step(B1(), Y(), b_rsrc, koff, e_ring + par * (8 * kFrag));                // A_p . F; fills (E, B_p') of kt
         koff += 8 * kFrag;
         par ^= 1;
-        half_step(B0(), Y(), f_rsrc, koff, a_raw + par * kRawSlot);                    // E . B_p'; fills (A_p, F) of kt + 1
+        slot = slot == kRawSlots - 1 ? 0 : slot + 1;
+        half_step(B0(), Y(), f_rsrc, koff, a_raw + slot * kRawSlot);                    // E . B_p'; fills (A_p, F) of kt + 1
         wait_lds();
         workgroup_barrier();
     }
