@@ -42,11 +42,12 @@ def parse():
     ap.add_argument("--config", default="5", choices=["1", "2", "3", "4", "5", "all"],
                     help="benchmark configuration (default 5, the headline); all: one JSON line per configuration")
     ap.add_argument("--path", default="limb", choices=["limb", "valu"])
-    ap.add_argument("--workload", default="matmul", choices=["matmul", "poly", "matmul128", "matmul32", "grouped"],
+    ap.add_argument("--workload", default="matmul", choices=["matmul", "poly", "matmul128", "matmul32", "grouped", "binary"],
                     help="matmul: the Beaver-matmul hot path (the benchmark); poly: completed-square polynomial "
                          "evaluation (Section 7.2 Eq. (4)) on the configuration's vector length; matmul128 / matmul32: the "
                          "Beaver matmul over the other two ring widths; grouped: the attention products of three "
-                         "LeViT-like stages submitted as one spin_beaver_matmul_grouped call against one call per product")
+                         "LeViT-like stages submitted as one spin_beaver_matmul_grouped call against one call per product; "
+                         "binary: XOR sharing, XOR open and the AND-triple update on 2^24 packed words")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time its replays (for the launch-bound small "
                          "configurations; the per-kernel figures then come from a separate eager pass)")
@@ -223,6 +224,59 @@ def bench_poly(args):
                       "higher_is_better": True, "vs_baseline": None, "dtype": "u64", "data": "synthetic",
                       "config": {"workload": "f1' of Section 7.2 Eq. (4) on %d elements, %d parties, p=14" % (count, n)},
                       "max_abs_error_vs_2^z": err, "stream_kernels": kernels}))
+
+
+def bench_binary(args):
+    """Side workload: the local work on binary shares (Section 4.1 binary sharing, Section 4.3 XOR) -- share two packed
+    64-lane words per element, the AND-triple update (the GF(2) Beaver multiplication), open the result -- on 2^24
+    words, 3 parties.  The opened result is checked against x & y of the inputs after the timed steps."""
+    import torch
+    from paper_2402_02320_amd import spin
+    n, count, seed = 3, 1 << 24, 7
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    x = torch.randint(-2 ** 63, 2 ** 63 - 1, (count,), dtype=torch.int64, device="cuda", generator=g)
+    y = torch.randint(-2 ** 63, 2 ** 63 - 1, (count,), dtype=torch.int64, device="cuda", generator=g)
+    a = torch.stack([spin.random(count, seed, 21, i) for i in range(n)])
+    b = torch.stack([spin.random(count, seed, 22, i) for i in range(n)])
+    c = spin.bshare(spin.bopen(a) & spin.bopen(b), n, seed, 23)
+    xs, ys, zs = torch.empty_like(a), torch.empty_like(a), torch.empty_like(a)
+    z = torch.empty_like(x)
+
+    def step():
+        spin.bshare(x, n, seed, 1, out=xs)
+        spin.bshare(y, n, seed, 2, out=ys)
+        spin.beaver_and(xs, ys, a, b, c, out=zs)
+        spin.bopen(zs, out=z)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    spin.profile_reset()
+    spin.profile_enable(True)
+    t_begin = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    spin.profile_enable(False)
+    ms = (t_end - t_begin) * 1e3 / args.steps
+    tot, cnt = spin.profile_read("binary")
+    spin.profile_reset()
+    if not torch.equal(z, x & y):
+        raise SystemExit("bench.py: the opened AND differs from x & y")
+    # words of 8 bytes per element and step: two sharings (1 in, n out each), the update (5n in, n out), the open (n in, 1 out)
+    words = 2 * (1 + n) + 6 * n + (n + 1)
+    print(json.dumps({"metric": "packed 64-lane binary-share AND evaluations/s (side workload)", "value": count / (ms * 1e-3),
+                      "unit": "words/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+                      "higher_is_better": True, "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+                      "config": {"workload": "bshare x, y; beaver_and; bopen on %d words, %d parties" % (count, n)},
+                      "parity": "opened result equals x & y on all words",
+                      "roofline": {"bound": "hbm", "achieved": words * 8.0 * count / (tot / args.steps * 1e-3) / 1e9,
+                                   "peak": 8000.0, "unit": "GB/s",
+                                   "frac": words * 8.0 * count / (tot / args.steps * 1e-3) / 8e12,
+                                   "kernel": "bshare, beaver_and, bopen kernels together",
+                                   "kernel_ms_per_step": tot / args.steps, "launches_per_step": cnt / args.steps,
+                                   "traffic": None}}))
 
 
 def bench_matmul_other_ring(args, bits):
@@ -628,6 +682,8 @@ def main():
         return bench_matmul_other_ring(args, 128 if args.workload == "matmul128" else 32)
     if args.workload == "grouped":
         return bench_grouped(args)
+    if args.workload == "binary":
+        return bench_binary(args)
     configs = [1, 2, 3, 4, 5] if args.config == "all" else [int(args.config)]
     for cfg in configs:
         print(json.dumps(run_config(args, cfg)), flush=True)
