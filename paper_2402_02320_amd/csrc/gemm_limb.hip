@@ -395,10 +395,12 @@ struct RowGemmArgs {
     int batch, M, N, K, KT, tilesN;
 };
 
-// Raw tile in LDS: 64 groups of 128 bytes, group 2 r + h = the 16 consecutive k (8 pieces of 16 bytes) of
-// row r, half h; piece q sits at position q ^ (r & 7) of its group, so that the 8 lanes that read the same
-// piece of 8 consecutive rows hit 8 different bank groups.  A direct-to-LDS load fills 1 KiB = 8 groups =
-// 4 rows x 256 bytes with whole 128-byte lines of memory.
+// Raw tile in LDS: 32 rows of 256 bytes = 16 pieces of 16 bytes (piece 8 h + q = the q-th pair of k of half h);
+// piece p of row r sits at position p ^ (r & 15) of its row, so that the 16 lanes that read the same piece of
+// 16 consecutive rows hit 16 different 16-byte bank groups of the 256 bytes the LDS serves per cycle (with the
+// swizzle over 8 positions only, rows r and r + 8 collided: a two-way conflict on every read).  In group
+// terms: the row's two 128-byte halves are swapped when bit 3 of r is set, and piece q sits at position
+// q ^ (r & 7) of its half.  A direct-to-LDS load fills 1 KiB = 4 rows x 256 bytes with whole lines of memory.
 constexpr int kRawTile = 32 * 32 * 8;
 constexpr int kRawSlot = 3 * 2 * kRawTile;               // X_j then A_j for up to three parties
 constexpr int kRawSlots = 3;                             // raw k-tiles in LDS: one in use, two in flight
@@ -451,18 +453,18 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
     lds_char *lds3 = (lds_char *)lds;
     lds_char *e_ring = lds3 + kRawSlots * kRawSlot;
     // this lane's 16 consecutive k of row lane % 32, half lane / 32, in a raw tile: piece q at raw_lane ^ (16 q)
-    const u32 raw_lane = (2 * (lane % 32) + lane / 32) * 128 + (lane % 8) * 16;
+    const u32 raw_lane = (2 * (lane % 32) + (lane / 32 ^ ((lane >> 3) & 1))) * 128 + (lane % 8) * 16;
 
     if (wave == NP) {
         // ---------------------------------------------------------------- producer
-        // load i, lane p: group 8 i + p / 8 -> row 4 i + p / 16, half (p / 8) % 2; position p % 8 holds piece
-        // (p % 8) ^ (row & 7); the lane fetches that piece of the row's 256 bytes
+        // load i, lane p: row 4 i + p / 16; its 128-byte slot (p / 8) % 2 holds the half (p / 8) % 2 ^ bit 3 of
+        // the row, position p % 8 of it the piece (p % 8) ^ (row & 7); the lane fetches that piece of the row's 256 bytes
         const size_t row_pitch = (size_t)g.K * 8;
         const bool k_edge = KT * 32 > g.K;               // the last k-tile is ragged
         u32 voff[8], voff_last[8];                       // per-lane byte offsets from the tile's first element
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int row = 4 * i + lane / 16, half = (lane / 8) % 2, piece = (lane % 8) ^ (row & 7);
+            const int row = 4 * i + lane / 16, half = ((lane / 8) % 2) ^ ((row >> 3) & 1), piece = (lane % 8) ^ (row & 7);
             const u32 off = (u32)(row * row_pitch) + half * 128 + piece * 16;     // K <= 16352: far below 2^32
             const bool row_ok = rb * 32 + row < g.M;
             const bool k_ok = (KT - 1) * 32 + 16 * half + 2 * piece < g.K;        // K is even
