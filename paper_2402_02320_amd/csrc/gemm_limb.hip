@@ -387,6 +387,13 @@ __global__ __launch_bounds__(256) void limb_gemm_grouped_kernel(GroupTable<GemmA
 // stage g % 2 (first half) and raw A_p(g+1) from raw slot (g+1) % 3 (second half); the producer reads raw
 // slot (g+1) % 3, writes E(g+1) to stage (g+1) % 2, refills raw slot g % 3 with k-tile g + 3 and waits for
 // k-tile g + 2, issued one iteration earlier: every load has two iterations to arrive.
+// Workgroups of a row-kernel launch: (row blocks over all batch entries, rounded up to a multiple of 8) x column tiles.
+__host__ __device__ inline long rows_grid(int batch, int M, int tilesN)
+{
+    const long rblocks = (long)batch * ((M + 31) / 32);
+    return (rblocks + 7) / 8 * 8 * tilesN;
+}
+
 struct RowGemmArgs {
     const u64 *X, *A;        // [n][batch][M][K]
     const char *packB;       // right fragment store [n+1][batch][2 tilesN][KT][8][1024]: slot 0 = F, 1 + i = B_i'
@@ -447,8 +454,14 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int lane = threadIdx.x % 64;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+    // Workgroup ids are dealt round-robin to the 8 XCDs: the column tiles of one block of rows get ids 8 apart,
+    // so they meet in one L2 and the raw tiles come from memory once (rows_grid pads the id space to whole
+    // groups of 8 row blocks; a workgroup of the padding leaves at once, all four waves together).
     const int rblocks = (g.M + 31) / 32;
-    const int rb = block % rblocks, tn = block / rblocks % g.tilesN, b = block / rblocks / g.tilesN;
+    const int tn = block / 8 % g.tilesN;
+    const long rblock = (long)(block / 8 / g.tilesN) * 8 + block % 8;        // over batch x rblocks
+    if (rblock >= (long)g.batch * rblocks) return;
+    const int rb = (int)(rblock % rblocks), b = (int)(rblock / rblocks);
     const int KT = g.KT;
     lds_char *lds3 = (lds_char *)lds;
     lds_char *e_ring = lds3 + kRawSlots * kRawSlot;
@@ -768,7 +781,7 @@ template <class T> inline bool rows_kernel_applies(const MatmulArgsT<T> &a, cons
     if (!std::is_same<T, u64>::value) return false;
     if (a.n > 3 || a.K % 2 != 0 || p.KT > Ring<u64>::max_chunk_tiles) return false;
     const int cus = compute_units();
-    const long rblocks = (long)a.batch * ceil_div(a.M, 32) * p.tilesN;
+    const long rblocks = rows_grid(a.batch, a.M, p.tilesN);
     if (rblocks > 0x7fffffffL) return false;
     const double cost_rows = (double)((rblocks + cus - 1) / cus) * (2 * p.KT + 8);
     const long tiles = (long)p.tilesM * p.tilesN * a.n * a.batch;
@@ -788,7 +801,7 @@ inline spin_status launch_rows(const MatmulArgs &a, const Plan &p, char *packB, 
         if (st != SPIN_OK) return st;
     }
     RowGemmArgs g{a.X, a.A, packB, a.C, a.Z, a.batch, a.M, a.N, a.K, p.KT, p.tilesN};
-    const unsigned grid = (unsigned)((long)a.batch * ceil_div(a.M, 32) * p.tilesN);
+    const unsigned grid = (unsigned)rows_grid(a.batch, a.M, p.tilesN);
     spin_status st = SPIN_OK;
     for_party_count(a.n, [&](auto np) {
         constexpr int NP = decltype(np)::value <= 3 ? decltype(np)::value : 3;   // n <= 3 is checked by the caller
@@ -910,7 +923,7 @@ spin_status launch_matmul_limb_grouped(int n, int groups, const MatmulArgs *a, v
         }
         if (rows_kernel_applies<u64>(m, p)) {
             rows.push_back(RowGemmArgs{m.X, m.A, packB, m.C, m.Z, m.batch, m.M, m.N, m.K, p.KT, p.tilesN});
-            row_blocks.push_back((unsigned)((long)m.batch * ceil_div(m.M, 32) * p.tilesN));
+            row_blocks.push_back((unsigned)rows_grid(m.batch, m.M, p.tilesN));
         } else {
             left.push_back(PackArgs<u64>{m.X, m.A, packA, n, m.batch, m.M, m.K, p.nblkA, p.KT});
             left_blocks.push_back(pack_left_blocks<WAVES>(p.nblkA, p.KT) * m.batch);
