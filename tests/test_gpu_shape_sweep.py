@@ -67,3 +67,25 @@ def test_sweep_ring128(path):
         want = r128.beaver_matmul(X, Y, A, B, C)
         got = spin.ring128.beaver_matmul(dev64(X), dev64(Y), dev64(A), dev64(B), dev64(C), path=path)
         assert (got.cpu().numpy().view(np.uint64) == want).all(), (n, batch, M, N, K)
+
+
+def test_sweep_row_kernel_domain():
+    # at most three parties, an even inner dimension, one to a few column tiles: the shapes the row-streaming limb
+    # kernel takes (inner dimensions of 1 .. 40 k-tiles walk every phase of its three-slot ring), plain and with
+    # the right operand stored transposed
+    rng = np.random.default_rng(2024)
+    for idx in range(120):
+        n, batch = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        M = int(rng.choice([1, 31, 32, 33, 64, 95, 100, 257, 1000])) if rng.random() < 0.5 else int(rng.integers(1, 600))
+        N = int(rng.choice([1, 31, 32, 33, 63, 64, 65, 96, 128, 130, 192])) if rng.random() < 0.6 else int(rng.integers(1, 200))
+        K = 2 * int(rng.integers(1, 130)) if rng.random() < 0.8 else 2 * int(rng.integers(100, 640))
+        r = np.random.default_rng(idx)
+        X = r.integers(0, 1 << 64, size=(n, batch, M, K), dtype=np.uint64)
+        Y = r.integers(0, 1 << 64, size=(n, batch, K, N), dtype=np.uint64)
+        A, B, C = oracle.dealer_matmul(n, batch, M, N, K, seed=idx)
+        want = oracle.beaver_matmul(X, Y, A, B, C)
+        got = spin.beaver_matmul(dev64(X), dev64(Y), dev64(A), dev64(B), dev64(C), path=spin.LIMB_MFMA)
+        assert (got.cpu().numpy().view(np.uint64) == want).all(), (n, batch, M, N, K)
+        Yt, Bt = (dev64(np.ascontiguousarray(t.transpose(0, 1, 3, 2))) for t in (Y, B))
+        got_t = spin.beaver_matmul(dev64(X), Yt, dev64(A), Bt, dev64(C), path=spin.LIMB_MFMA, y_transposed=True)
+        assert torch.equal(got, got_t), (n, batch, M, N, K)
