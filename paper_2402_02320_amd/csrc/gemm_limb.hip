@@ -387,6 +387,11 @@ __global__ __launch_bounds__(256) void limb_gemm_grouped_kernel(GroupTable<GemmA
 // stage g % 2 (first half) and raw A_p(g+1) from raw slot (g+1) % 3 (second half); the producer reads raw
 // slot (g+1) % 3, writes E(g+1) to stage (g+1) % 2, refills raw slot g % 3 with k-tile g + 3 and waits for
 // k-tile g + 2, issued one iteration earlier: every load has two iterations to arrive.
+// A launch has at most one workgroup per CU (more would only queue: a workgroup takes a whole CU); each walks
+// its share of the (row block, column tile) items, and g above counts the k-tiles of all its items in one
+// sequence: the producer runs ahead across item boundaries, so that the first tiles of the next item arrive
+// and its E(0) is opened while the consumers recombine and store the current one.  Two more barriers per item
+// frame the consumers' conversion of the item's first A_p tile.
 // Workgroups of a row-kernel launch: (row blocks over all batch entries, rounded up to a multiple of 8) x column tiles.
 __host__ __device__ inline long rows_grid(int batch, int M, int tilesN)
 {
@@ -449,7 +454,7 @@ typedef __attribute__((address_space(3))) const u64x2 lds_u64x2;
 typedef __attribute__((address_space(3))) const v4i lds_v4i;
 
 template <int NP>
-__device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsigned block)
+__device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsigned first_item, unsigned item_stride)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int lane = threadIdx.x % 64;
@@ -457,11 +462,18 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
     // Workgroup ids are dealt round-robin to the 8 XCDs: the column tiles of one block of rows get ids 8 apart,
     // so they meet in one L2 and the raw tiles come from memory once (rows_grid pads the id space to whole
     // groups of 8 row blocks; a workgroup of the padding leaves at once, all four waves together).
+    // A workgroup walks the items first_item, first_item + item_stride, ... (the stride is a multiple of 8, so all
+    // of them belong to one XCD); the items of the padding have the highest ids, so the valid ones come first.
     const int rblocks = (g.M + 31) / 32;
-    const int tn = block / 8 % g.tilesN;
-    const long rblock = (long)(block / 8 / g.tilesN) * 8 + block % 8;        // over batch x rblocks
-    if (rblock >= (long)g.batch * rblocks) return;
-    const int rb = (int)(rblock % rblocks), b = (int)(rblock / rblocks);
+    // Item i = column tile (i / 8) % tilesN of row block 8 (i / 8 / tilesN) + i % 8 (row blocks counted over all batch
+    // entries; all counts are below 2^31, which the host checks).  With x = first_item % 8 the row block is valid
+    // while i / (8 tilesN) < ceil((row blocks - x) / 8).
+    const unsigned rblocks_all = (unsigned)g.batch * (unsigned)rblocks;
+    auto rblock_of = [&](unsigned item) -> unsigned { return item / 8 / (unsigned)g.tilesN * 8 + item % 8; };
+    const unsigned x = first_item % 8;
+    const unsigned limit = rblocks_all > x ? (rblocks_all - x + 7) / 8 * 8 * (unsigned)g.tilesN : 0;
+    const int n_items = first_item < limit ? (int)((limit - 1 - first_item) / item_stride) + 1 : 0;
+    if (n_items == 0) return;                            // all four waves together
     const int KT = g.KT;
     lds_char *lds3 = (lds_char *)lds;
     lds_char *e_ring = lds3 + kRawSlots * kRawSlot;
@@ -474,31 +486,55 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
         // the row, position p % 8 of it the piece (p % 8) ^ (row & 7); the lane fetches that piece of the row's 256 bytes
         const size_t row_pitch = (size_t)g.K * 8;
         const bool k_edge = KT * 32 > g.K;               // the last k-tile is ragged
-        u32 voff[8], voff_last[8];                       // per-lane byte offsets from the tile's first element
+        u32 off[8];                                      // per-lane byte offsets from the tile's first element
+        u32 k_ok = 0;                                    // bit i: load i of this lane stays inside K in the last k-tile
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int row = 4 * i + lane / 16, half = ((lane / 8) % 2) ^ ((row >> 3) & 1), piece = (lane % 8) ^ (row & 7);
-            const u32 off = (u32)(row * row_pitch) + half * 128 + piece * 16;     // K <= 16352: far below 2^32
-            const bool row_ok = rb * 32 + row < g.M;
-            const bool k_ok = (KT - 1) * 32 + 16 * half + 2 * piece < g.K;        // K is even
-            voff[i] = row_ok ? off : 0;
-            voff_last[i] = row_ok && k_ok ? off : 0;
+            off[i] = (u32)(row * row_pitch) + half * 128 + piece * 16;            // K <= 16352: far below 2^32
+            if ((KT - 1) * 32 + 16 * half + 2 * piece < g.K) k_ok |= 1u << i;     // K is even
         }
-        const size_t tile0 = ((size_t)b * g.M + (size_t)rb * 32) * row_pitch;     // party 0, k-tile 0
         const size_t party_stride = (size_t)g.batch * g.M * row_pitch;
         const u32 raw0 = (u32)(uintptr_t)lds3;
-        auto issue = [&](int kt) {                       // all parties' tiles of k-tile kt -> raw slot kt % 3
-            const u32 dst = raw0 + (kt % kRawSlots) * kRawSlot;
-            const bool last = k_edge && kt + 1 == KT;
+        // The k-tiles of all items form one sequence t = 0, 1, ..: tile t lives in raw slot t % 3, E(t) in fragment
+        // stage t % 2, and the producer runs up to three tiles ahead of the consumers across item boundaries, so
+        // the first tiles of the next item arrive, and its E(0) is opened, while the consumers finish this one.
+        const int total = n_items * KT;
+        unsigned is_item = first_item;                   // issue cursor: item, k-tile within it, raw slot
+        int is_k = 0;
+        u32 is_slot = 0;
+        size_t is_tile0 = 0;
+        int is_row0 = 0;
+        auto set_issue_item = [&]() {
+            const unsigned rblock = rblock_of(is_item);
+            is_row0 = (int)(rblock % (unsigned)rblocks) * 32;
+            is_tile0 = ((size_t)(rblock / (unsigned)rblocks) * g.M + (size_t)is_row0) * row_pitch;      // party 0, k-tile 0
+        };
+        set_issue_item();
+        auto issue = [&]() {                             // all parties' tiles of the cursor's k-tile -> its raw slot
+            const u32 dst = raw0 + is_slot * kRawSlot;
+            const bool last = k_edge && is_k + 1 == KT;
+            u32 voff[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const bool ok = is_row0 + 4 * i + lane / 16 < g.M && (!last || ((k_ok >> i) & 1));
+                voff[i] = ok ? off[i] : 0;
+            }
 #pragma unroll
             for (int j = 0; j < NP; ++j) {
-                const size_t off = tile0 + j * party_stride + (size_t)kt * 256;
-                if (last) load_raw_pair((const char *)g.X + off, (const char *)g.A + off, dst + j * (2 * kRawTile), voff_last);
-                else load_raw_pair((const char *)g.X + off, (const char *)g.A + off, dst + j * (2 * kRawTile), voff);
+                const size_t o = is_tile0 + j * party_stride + (size_t)is_k * 256;
+                load_raw_pair((const char *)g.X + o, (const char *)g.A + o, dst + j * (2 * kRawTile), voff);
+            }
+            is_slot = is_slot == kRawSlots - 1 ? 0 : is_slot + 1;
+            if (++is_k == KT) {                          // on to the next item (past the last one nothing is issued)
+                is_k = 0;
+                is_item += item_stride;
+                set_issue_item();
             }
         };
-        auto open_tile = [&](int kt) {                   // E(kt) from raw slot kt % 3 -> fragment stage kt % 2
-            lds_char *slot = lds3 + (kt % kRawSlots) * kRawSlot;
+        u32 op_slot = 0, op_stage = 0;                   // open cursor
+        auto open_tile = [&]() {                         // E of the cursor's tile from its raw slot -> its fragment stage
+            lds_char *slot = lds3 + op_slot * kRawSlot;
             u64x2 opened[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) opened[q] = (u64x2)(0);
@@ -516,33 +552,40 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
                 w[2 * q] = to_digits<u64>(opened[q].x);
                 w[2 * q + 1] = to_digits<u64>(opened[q].y);
             }
-            store_digit_rows<u64>(w, lds + kRawSlots * kRawSlot + (kt % 2) * (8 * kFrag) + lane * 16);
+            store_digit_rows<u64>(w, lds + kRawSlots * kRawSlot + op_stage * (8 * kFrag) + lane * 16);
+            op_slot = op_slot == kRawSlots - 1 ? 0 : op_slot + 1;
+            op_stage ^= 1;
         };
         // Two k-tiles are in flight while one is in use.  Loads return in order, so waiting until at most one
         // k-tile's loads (16 NP) are outstanding means that everything older has landed; before a k-tile is
         // issued the count is brought down to 15, which keeps it within the wave's 6-bit counter.
-        auto issue_ahead = [&](int kt) {                 // issue k-tile kt (if any); on return every older one has landed
-            if (kt < KT) {
+        auto issue_ahead = [&](int t) {                  // issue tile t (if any); on return every older one has landed
+            if (t < total) {
                 wait_loads<15>();
-                issue(kt);
+                issue();
                 wait_loads<16 * NP>();
             } else {
                 wait_loads<0>();
             }
         };
-        issue(0);
+        issue();
         wait_loads<0>();
-        if (KT > 1) issue(1);
-        open_tile(0);
+        if (total > 1) issue();
+        open_tile();
         issue_ahead(2);
         wait_lds();
-        workgroup_barrier();                             // raw tiles 0 and 1 and E(0) are in LDS
-        workgroup_barrier();                             // the consumers have taken A_p(0) out of raw slot 0
-        for (int kt = 0; kt < KT; ++kt) {                // the barrier that ends iteration kt: raw tile kt + 2 and E(kt + 1) are in LDS
-            if (kt + 1 < KT) open_tile(kt + 1);
-            issue_ahead(kt + 3);                         // into the slot of k-tile kt, which nobody reads any more
-            wait_lds();
+        int t = 0;
+        for (int item = 0; item < n_items; ++item) {
+            // before these two: raw tiles t and t + 1 and E(t) are in LDS (from the start-up above or from the
+            // last iteration of the item before); between them the consumers take A_p(t) out of its raw slot
             workgroup_barrier();
+            workgroup_barrier();
+            for (int kt = 0; kt < KT; ++kt, ++t) {       // the barrier that ends iteration t: raw tile t + 2 and E(t + 1) are in LDS
+                if (t + 1 < total) open_tile();
+                issue_ahead(t + 3);                      // into the slot of tile t, which nobody reads any more
+                wait_lds();
+                workgroup_barrier();
+            }
         }
         return;
     }
@@ -554,17 +597,9 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
     // the lane's 16 bytes as the only vector offset, the k-tile and column block in a scalar offset, the
     // digit as the immediate -- so the 32 loads of a k-tile need no per-lane address arithmetic.
     const u32 cb_stride = (u32)KT * (8 * kFrag);         // from column block 0 to column block 1 (< 2^22)
-    const char *f_base = g.packB + ((size_t)b * g.tilesN + tn) * 2 * cb_stride;                              // F
-    const char *b_base = g.packB + (((size_t)(1 + party) * g.batch + b) * g.tilesN + tn) * 2 * cb_stride;    // B_p'
-    const __amdgpu_buffer_rsrc_t f_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)f_base, 0, 2 * cb_stride, 0x00020000);
-    const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)b_base, 0, 2 * cb_stride, 0x00020000);
     lds_char *a_raw = lds3 + party * (2 * kRawTile) + kRawTile;      // raw A_p in raw slot 0
 
     v16i acc[2][8];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int d = 0; d < 8; ++d) acc[j][d] = (v16i)(0);
     // fragment registers: [0..15] right (column block q / 8, digit q % 8), [16..23] left (digit q - 16);
     // buffer 0 serves the (E, B_p') half step, buffer 1 the (A_p, F) half step
     v4i fr[2][24];
@@ -649,18 +684,31 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
     using B0 = std::integral_constant<int, 0>;
     using B1 = std::integral_constant<int, 1>;
 
+    u32 par = 0;                                         // t % 2 and t % 3 of the current tile of the workgroup's sequence
+    u32 slot = 0;
+    unsigned item_id = first_item;
+    for (int item = 0; item < n_items; ++item, item_id += item_stride) {
+    const int tn = (int)(item_id / 8 % (unsigned)g.tilesN);
+    const unsigned rblock = rblock_of(item_id);
+    const int rb = (int)(rblock % (unsigned)rblocks), b = (int)(rblock / (unsigned)rblocks);
+    const char *f_base = g.packB + ((size_t)b * g.tilesN + tn) * 2 * cb_stride;                              // F
+    const char *b_base = g.packB + (((size_t)(1 + party) * g.batch + b) * g.tilesN + tn) * 2 * cb_stride;    // B_p'
+    const __amdgpu_buffer_rsrc_t f_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)f_base, 0, 2 * cb_stride, 0x00020000);
+    const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)b_base, 0, 2 * cb_stride, 0x00020000);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int d = 0; d < 8; ++d) acc[j][d] = (v16i)(0);
 #pragma unroll
     for (int q = 0; q < 16; ++q) fr[1][q] = right_fragment(q, f_rsrc, 0);   // in flight while the producer starts up
-    workgroup_barrier();                                 // raw tiles 0 and 1 and E(0) are in LDS
+    workgroup_barrier();                                 // raw tiles t and t + 1 and E(t) are in LDS
 #pragma unroll
     for (int c = 0; c < 4; ++c)
 #pragma unroll
-        for (int step = 0; step < 7; ++step) convert_step(c, step, a_raw);
+        for (int step = 0; step < 7; ++step) convert_step(c, step, a_raw + slot * kRawSlot);
     wait_lds();
-    workgroup_barrier();                                 // raw slot 0 may be refilled
+    workgroup_barrier();                                 // the raw slot of tile t may be refilled
     u32 koff = 0;                                        // byte offset of the current k-tile in a fragment stream
-    u32 par = 0;                                         // kt % 2
-    u32 slot = 0;                                        // kt % 3
     for (int kt = 0; kt + 1 < KT; ++kt) {                // the last k-tile is peeled: no branch around MFMAs
         half_step(B1(), Y(), b_rsrc, koff, e_ring + par * (8 * kFrag));                // A_p . F; fills (E, B_p') of kt
         koff += 8 * kFrag;
@@ -671,7 +719,7 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
         workgroup_barrier();
     }
     koff = (u32)(KT - 1) * (8 * kFrag);                  // restated from the argument, so that it stays scalar
-    half_step(B1(), Y(), b_rsrc, koff, e_ring + ((KT - 1) % 2) * (8 * kFrag));
+    half_step(B1(), Y(), b_rsrc, koff, e_ring + par * (8 * kFrag));
 
     // C_p is fetched under the last half step (the fragment buffer that half step would have filled is free):
     // the epilogue then starts with its operands at hand.  Rows and columns beyond the matrix are redirected
@@ -693,6 +741,8 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
     __builtin_amdgcn_sched_barrier(0);
     half_step(B0(), F(), f_rsrc, koff, a_raw);
     workgroup_barrier();
+    par ^= 1;                                            // past the item's last tile
+    slot = slot == kRawSlots - 1 ? 0 : slot + 1;
 
     // recombine the diagonals, add C_p, store (same structure as the tile kernel's epilogue)
 #pragma unroll
@@ -715,19 +765,20 @@ __device__ __forceinline__ void limb_gemm_rows_body(const RowGemmArgs &g, unsign
                 if (row_of(r) < g.M && col < g.N) Zm[(size_t)row_of(r) * g.N + col] = v[r];
         }
     }
+    }                                                    // next item
 }
 
 template <int NP>
 __global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_kernel(RowGemmArgs g)
 {
-    limb_gemm_rows_body<NP>(g, blockIdx.x);
+    limb_gemm_rows_body<NP>(g, blockIdx.x, gridDim.x);
 }
 
 template <int NP>
 __global__ __launch_bounds__(64 * (NP + 1)) void limb_gemm_rows_grouped_kernel(GroupTable<RowGemmArgs> t)
 {
     const int gi = group_of(t, blockIdx.x);
-    limb_gemm_rows_body<NP>(t.e[gi], blockIdx.x - t.first[gi]);
+    limb_gemm_rows_body<NP>(t.e[gi], blockIdx.x - t.first[gi], 0x7fffffffu);
 }
 
 // ------------------------------------------------------------------ host ---
@@ -801,7 +852,11 @@ inline spin_status launch_rows(const MatmulArgs &a, const Plan &p, char *packB, 
         if (st != SPIN_OK) return st;
     }
     RowGemmArgs g{a.X, a.A, packB, a.C, a.Z, a.batch, a.M, a.N, a.K, p.KT, p.tilesN};
-    const unsigned grid = (unsigned)rows_grid(a.batch, a.M, p.tilesN);
+    // One workgroup fits a CU, so more workgroups than CUs only queue: launch one per CU (a multiple of 8, so that
+    // an item keeps its XCD) and let each walk its items, the producer running ahead across item boundaries.
+    const unsigned items = (unsigned)rows_grid(a.batch, a.M, p.tilesN);
+    const unsigned resident = (unsigned)std::max(8, compute_units() / 8 * 8);
+    const unsigned grid = items > resident && ((long)items / resident + 1) * p.KT < (1L << 30) ? resident : items;
     spin_status st = SPIN_OK;
     for_party_count(a.n, [&](auto np) {
         constexpr int NP = decltype(np)::value <= 3 ? decltype(np)::value : 3;   // n <= 3 is checked by the caller

@@ -217,6 +217,8 @@ def test_few_tiles_and_a_long_inner_dimension(n, batch, M, N, K):
 ROW_SHAPES = [(3, 1, 32, 64, 32), (3, 1, 64, 64, 64), (2, 1, 33, 31, 34), (1, 1, 100, 64, 96), (3, 2, 130, 57, 46),
               (3, 1, 1, 1, 2), (2, 3, 95, 64, 128), (3, 1, 4096, 64, 576), (3, 64, 128, 64, 128), (1, 2, 257, 33, 1000),
               (3, 1, 8192, 64, 70), (2, 1, 9000, 48, 2048), (3, 1, 70, 64, 160), (2, 2, 40, 50, 192), (3, 1, 33, 64, 226),
+              # more row blocks than CUs: a workgroup walks several of them, its producer running ahead across the boundary
+              (3, 1, 9000, 64, 32), (2, 3, 3000, 130, 40), (1, 1, 20000, 33, 6), (3, 1, 8500, 64, 96), (2, 70, 128, 100, 64),
               # a few column tiles and a short inner dimension (the attention shapes): one pass per column tile
               (3, 64, 128, 128, 64), (3, 2, 100, 130, 40), (2, 1, 64, 192, 32), (3, 8, 196, 196, 64)]
 
